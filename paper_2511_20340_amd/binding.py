@@ -1,0 +1,98 @@
+"""ctypes mirror of include/specformer.h.  Argument marshalling only."""
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libspecformer.so")
+
+SF_OK, SF_EINVAL, SF_ECAPACITY, SF_ESTATE, SF_EHIP, SF_EUNSUPPORTED = range(6)
+SF_BF16, SF_F32 = 0, 1
+SF_MASK_CAUSAL, SF_MASK_BIDIR = 0, 1
+
+EXPORTS = [
+    "sf_create", "sf_destroy", "sf_workspace_bytes", "sf_kv_cache_bytes", "sf_bind", "sf_draft_step",
+    "sf_verify_step", "sf_accept_commit", "sf_kv_import", "sf_kv_export", "sf_attention_workspace_bytes",
+    "sf_op_attention", "sf_op_linear", "sf_op_rmsnorm", "sf_op_rope_kv_append", "sf_op_silu_mul",
+    "sf_argmax_workspace_bytes", "sf_op_argmax", "sf_strerror", "sf_last_hip_error", "sf_version",
+]
+
+vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+
+
+class ModelCfg(C.Structure):
+    _fields_ = [(n, i32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] \
+        + [("rope_theta", C.c_float), ("rms_eps", C.c_float), ("dtype", i32)]
+
+
+class TargetWeights(C.Structure):
+    _fields_ = [("embed", vp), ("lm_head", vp), ("final_norm", vp)] + \
+        [(n, C.POINTER(vp)) for n in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")]
+
+
+class DraftWeights(C.Structure):
+    _fields_ = [(n, vp) for n in ("group_norm", "w_ds", "pos_norm", "w_pos", "b_pos", "attn_norm", "wqkv", "wo",
+                                  "ffn_norm", "w_gate_up", "w_down", "out_norm")]
+
+
+class State(C.Structure):
+    _fields_ = [("B", i32), ("cap", i32), ("tk", vp), ("tv", vp), ("dk", vp), ("dv", vp), ("kv_len", vp),
+                ("pending", vp), ("hooks", vp), ("n_new", vp), ("cu_new", vp), ("workspace", vp),
+                ("workspace_bytes", sz)]
+
+
+class SfError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__(f"{what}: {lib().sf_strerror(status).decode()} (status {status})")
+
+
+_lib = None
+
+
+def lib():
+    """Load the HIP library; there is no fallback path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_20340_amd.build` "
+                           "(or __graft_entry__.build()); there is no CPU fallback")
+    L = C.CDLL(LIB_PATH)
+    P = C.POINTER
+    L.sf_create.argtypes = [P(ModelCfg), P(ModelCfg), i32, i32, P(vp)]
+    L.sf_destroy.argtypes = [vp]
+    L.sf_workspace_bytes.argtypes = [vp, i32, i32, i32]
+    L.sf_workspace_bytes.restype = sz
+    L.sf_kv_cache_bytes.argtypes = [vp, i32, i32, i32]
+    L.sf_kv_cache_bytes.restype = sz
+    L.sf_bind.argtypes = [vp, P(TargetWeights), P(DraftWeights)]
+    L.sf_draft_step.argtypes = [vp, P(State), i32, i32, i32, vp, vp]
+    L.sf_verify_step.argtypes = [vp, P(State), i32, vp, i32, vp, vp]
+    L.sf_accept_commit.argtypes = [vp, P(State), i32, vp, vp, vp, vp, vp, vp]
+    L.sf_kv_import.argtypes = [vp, vp, vp, i32, i32, i32, vp]
+    L.sf_kv_export.argtypes = [vp, vp, vp, i32, i32, i32, vp]
+    L.sf_attention_workspace_bytes.argtypes = [vp, i32, i32, i32]
+    L.sf_attention_workspace_bytes.restype = sz
+    L.sf_op_attention.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
+    L.sf_op_linear.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
+    L.sf_op_rmsnorm.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
+    L.sf_op_rope_kv_append.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+    L.sf_op_silu_mul.argtypes = [vp, vp, vp, i32, i32, vp]
+    L.sf_argmax_workspace_bytes.argtypes = [i32]
+    L.sf_argmax_workspace_bytes.restype = sz
+    L.sf_op_argmax.argtypes = [vp, vp, i32, i32, vp, vp, sz, vp]
+    L.sf_strerror.argtypes = [i32]
+    L.sf_strerror.restype = C.c_char_p
+    L.sf_last_hip_error.argtypes = [vp]
+    L.sf_version.restype = C.c_char_p
+    for name in EXPORTS:
+        f = getattr(L, name)
+        if f.restype is C.c_int:  # status-returning entry points
+            f.restype = i32
+    _lib = L
+    return L
+
+
+def check(status, what):
+    if status != SF_OK:
+        raise SfError(status, what)

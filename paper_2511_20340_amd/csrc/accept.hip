@@ -1,0 +1,136 @@
+// Lossless greedy acceptance for gfx950: arg-max over the vocabulary (the only HBM-heavy part: one
+// streaming read of the fp32 logits), draft/target comparison, longest accepted prefix, commit of
+// lengths / pending tokens, exclusive scan of the accept lengths.
+//
+// Pass 1 splits every logits row into ARGMAX_SEGS segments so that B*(k+1) rows give thousands of
+// workgroups; pass 2 is one workgroup that finishes the arg-max, compares, commits and scans.
+// Ties resolve to the lowest index; NaN never wins; a row without any comparable value gives 0.
+#include "sf_internal.h"
+#include <limits.h>
+
+namespace sf {
+namespace {
+
+struct Best {
+  float v;
+  int32_t i;
+};
+__device__ __forceinline__ void take(Best &b, float v, int32_t i) {
+  if (v != v) return;
+  if (v > b.v || (v == b.v && i < b.i)) { b.v = v; b.i = i; }
+}
+__device__ __forceinline__ Best better(Best a, Best b) {
+  return (b.v > a.v || (b.v == a.v && b.i < a.i)) ? b : a;
+}
+
+__global__ __launch_bounds__(256) void argmax_partial_kernel(const float *__restrict__ logits, int V,
+                                                             float *__restrict__ pmax, int32_t *__restrict__ pidx) {
+  __shared__ float sv[4];
+  __shared__ int32_t si[4];
+  const int seg = blockIdx.x, row = blockIdx.y;
+  int seg_len = (V + ARGMAX_SEGS - 1) / ARGMAX_SEGS;
+  seg_len = (seg_len + 3) & ~3;
+  const int lo = seg * seg_len, hi = min(V, lo + seg_len);
+  const float *x = logits + (size_t)row * V;
+  Best b{-__builtin_huge_valf(), INT_MAX};
+  if ((V & 3) == 0) {
+    for (int i = lo + threadIdx.x * 4; i < hi; i += 1024) {
+      const float4 v = *reinterpret_cast<const float4 *>(x + i);
+      take(b, v.x, i); take(b, v.y, i + 1); take(b, v.z, i + 2); take(b, v.w, i + 3);
+    }
+  } else {
+    for (int i = lo + threadIdx.x; i < hi; i += 256) take(b, x[i], i);
+  }
+  for (int o = 32; o; o >>= 1) {
+    Best other{__shfl_xor(b.v, o), __shfl_xor(b.i, o)};
+    b = better(b, other);
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) { sv[wave] = b.v; si[wave] = b.i; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) b = better(b, Best{sv[w], si[w]});
+    pmax[row * ARGMAX_SEGS + seg] = b.v;
+    pidx[row * ARGMAX_SEGS + seg] = b.i;
+  }
+}
+
+__device__ __forceinline__ int32_t row_argmax(const float *pmax, const int32_t *pidx, int row) {
+  Best b{-__builtin_huge_valf(), INT_MAX};
+  for (int s = 0; s < ARGMAX_SEGS; ++s) b = better(b, Best{pmax[row * ARGMAX_SEGS + s], pidx[row * ARGMAX_SEGS + s]});
+  return b.i == INT_MAX ? 0 : b.i;
+}
+
+__global__ void argmax_final_kernel(const float *__restrict__ pmax, const int32_t *__restrict__ pidx, int M,
+                                    int32_t *__restrict__ ids) {
+  const int row = blockIdx.x * blockDim.x + threadIdx.x;
+  if (row < M) ids[row] = row_argmax(pmax, pidx, row);
+}
+
+// One workgroup.  Thread t owns the sequences [t*per, (t+1)*per).
+__global__ __launch_bounds__(256) void accept_kernel(const float *__restrict__ pmax, const int32_t *__restrict__ pidx,
+                                                     const int32_t *__restrict__ draft,
+                                                     const int32_t *__restrict__ force_len,
+                                                     int32_t *__restrict__ accept_len, int32_t *__restrict__ out_tokens,
+                                                     int32_t *__restrict__ kv_len, int32_t *__restrict__ pending,
+                                                     int32_t *__restrict__ n_new, int32_t *__restrict__ cu_new, int B,
+                                                     int k) {
+  __shared__ int32_t scan[256];
+  const int q = k + 1;
+  const int per = (B + 255) / 256;
+  const int b0 = threadIdx.x * per, b1 = min(B, b0 + per);
+  int32_t local = 0;
+  for (int b = b0; b < b1; ++b) {
+    int32_t p[16];
+    for (int i = 0; i < q; ++i) p[i] = row_argmax(pmax, pidx, b * q + i);
+    int a;
+    if (force_len) {
+      a = min(max(force_len[b], 0), q);
+    } else {
+      int n = 0;
+      while (n < k && draft[b * k + n] == p[n]) ++n;
+      a = n + 1;
+    }
+    for (int i = 0; i < q; ++i) out_tokens[b * q + i] = i < a ? p[i] : -1;
+    accept_len[b] = a;
+    if (a > 0) pending[b] = p[a - 1];
+    kv_len[b] += a;
+    n_new[b] = a;
+    local += a;
+  }
+  scan[threadIdx.x] = local;
+  __syncthreads();
+  for (int o = 1; o < 256; o <<= 1) {  // inclusive Hillis-Steele scan
+    const int32_t v = threadIdx.x >= o ? scan[threadIdx.x - o] : 0;
+    __syncthreads();
+    scan[threadIdx.x] += v;
+    __syncthreads();
+  }
+  int32_t run = scan[threadIdx.x] - local;  // exclusive offset of this thread's first sequence
+  for (int b = b0; b < b1; ++b) {
+    cu_new[b] = run;
+    run += n_new[b];
+  }
+  if (b1 == B && b0 < B) cu_new[B] = run;
+  if (B == 0 && threadIdx.x == 0) cu_new[0] = 0;
+}
+
+}  // namespace
+
+hipError_t launch_argmax_partial(const float *logits, int M, int V, float *pmax, int32_t *pidx, hipStream_t s) {
+  argmax_partial_kernel<<<dim3(ARGMAX_SEGS, M), 256, 0, s>>>(logits, V, pmax, pidx);
+  return hipGetLastError();
+}
+
+hipError_t launch_argmax_final(const float *pmax, const int32_t *pidx, int M, int32_t *ids, hipStream_t s) {
+  argmax_final_kernel<<<(M + 255) / 256, 256, 0, s>>>(pmax, pidx, M, ids);
+  return hipGetLastError();
+}
+
+hipError_t launch_accept(const AcceptArgs &a, hipStream_t s) {
+  accept_kernel<<<1, 256, 0, s>>>(a.pmax, a.pidx, a.draft, a.force_len, a.accept_len, a.out_tokens, a.kv_len,
+                                  a.pending, a.n_new, a.cu_new, a.B, a.k);
+  return hipGetLastError();
+}
+
+}  // namespace sf

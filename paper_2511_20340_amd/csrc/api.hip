@@ -1,0 +1,449 @@
+// C ABI of libspecformer: context, argument validation, workspace planning and the three step
+// schedulers (draft / verify / accept) that enqueue the HIP kernels on the caller's stream.
+#include <math.h>
+#include <string.h>
+#include <new>
+#include <vector>
+#include "sf_internal.h"
+
+using namespace sf;
+
+struct sf_ctx {
+  sf_model_cfg tc, dc;
+  int max_B, max_k;
+  bool bound, has_draft;
+  sf_target_weights tw;
+  sf_draft_weights dw;
+  std::vector<const void *> attn_norm, wqkv, wo, ffn_norm, w_gate_up, w_down;
+  mutable int hip_err;
+};
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+size_t esize(int dtype) { return dtype == SF_BF16 ? 2 : 4; }
+
+// Workspace arena.  Buffers are sized for the larger of the verify (B*(k+1) rows), draft-context
+// (B*(max_k+1) rows) and draft-slot (B*k rows) uses; draft and verify run back to back on one
+// stream, so they share it.
+struct Arena {
+  size_t h, a, qkv, qr, ao, gu, act, table, part_o, part_ml, pmax, pidx;  // shared
+  size_t f4, x, kvc, xl, s0, dlogits;                                    // draft only
+  size_t total;
+};
+
+Arena plan(const sf_ctx *c, int B, int k, int cap) {
+  const sf_model_cfg &m = c->tc;
+  const size_t es = esize(m.dtype);
+  const size_t qm = c->max_k + 1;
+  const size_t M = (size_t)B * (k + 1), Mh = (size_t)B * qm, Ms = (size_t)B * (k > 0 ? k : 1);
+  const size_t Mx = M > Mh ? M : Mh;
+  const size_t d = m.d_model, F = m.d_ffn, V = m.vocab;
+  const size_t nq = (size_t)m.n_q_heads * m.head_dim, nkv = (size_t)m.n_kv_heads * m.head_dim;
+  Arena a;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += up(bytes); return o; };
+  a.h = take(M * d * es);
+  a.a = take(Mx * d * es);
+  a.qkv = take(M * (nq + 2 * nkv) * es);
+  a.qr = take(M * nq * es);
+  a.ao = take(M * nq * es);
+  a.gu = take(M * 2 * F * sizeof(float));
+  a.act = take(M * F * es);
+  a.table = take(Mx * (m.head_dim / 2) * sizeof(float2));
+  const int G = m.n_q_heads / m.n_kv_heads;
+  size_t part = m.dtype == SF_BF16 ? attn_workspace_bytes(B, m.n_kv_heads, m.head_dim, G, k + 1, cap) : 0;
+  const size_t rows_part = part / ((m.head_dim + 2) * sizeof(float));
+  a.part_o = take(rows_part * m.head_dim * sizeof(float));
+  a.part_ml = take(rows_part * 2 * sizeof(float));
+  a.pmax = take(Mx * ARGMAX_SEGS * sizeof(float));
+  a.pidx = take(Mx * ARGMAX_SEGS * sizeof(int32_t));
+  a.f4 = take(Mh * 4 * d * es);
+  a.x = take(Mh * d * es);
+  a.kvc = take(Mh * 2 * nkv * es);
+  a.xl = take((size_t)B * d * es);
+  a.s0 = take(Ms * d * es);
+  a.dlogits = take(Ms * V * sizeof(float));
+  a.total = off;
+  return a;
+}
+
+bool same_shape(const sf_model_cfg &a, const sf_model_cfg &b) {
+  return a.d_model == b.d_model && a.n_q_heads == b.n_q_heads && a.n_kv_heads == b.n_kv_heads &&
+         a.head_dim == b.head_dim && a.d_ffn == b.d_ffn && a.vocab == b.vocab && a.dtype == b.dtype &&
+         a.rope_theta == b.rope_theta && a.rms_eps == b.rms_eps;
+}
+
+sf_status check_attn_shape(const sf_model_cfg &m, int n_q) {
+  const int G = m.n_q_heads / m.n_kv_heads;
+  if (m.dtype == SF_BF16) {
+    if (G * n_q > 64) return SF_EUNSUPPORTED;
+  } else {
+    if (n_q * m.head_dim > 2048) return SF_EUNSUPPORTED;
+  }
+  return SF_OK;
+}
+
+struct Run {
+  const sf_ctx *c;
+  hipStream_t s;
+  sf_status st = SF_OK;
+  bool ok(hipError_t e) {
+    if (st != SF_OK) return false;
+    if (e != hipSuccess) { c->hip_err = (int)e; st = SF_EHIP; return false; }
+    return true;
+  }
+};
+
+void gemm(Run &r, int dtype, const void *x, const void *w, const void *bias, const void *res, void *y, int M, int N,
+          int K, int out_f32) {
+  if (r.st != SF_OK) return;
+  GemmArgs g{x, w, bias, res, y, M, N, K, out_f32};
+  r.ok(dtype == SF_BF16 ? launch_gemm_bf16(g, r.s) : launch_gemm_f32(g, r.s));
+}
+
+void norm(Run &r, const sf_model_cfg &m, const void *x, const void *gain, void *y, int M, int n_gain = 1,
+          int map = 0, int q = 1, int q_max = 1, const int32_t *n_new = nullptr) {
+  if (r.st != SF_OK) return;
+  NormArgs n{x, gain, y, M, m.d_model, n_gain, m.rms_eps, map, q, q_max, n_new};
+  r.ok(launch_rmsnorm(n, m.dtype, r.s));
+}
+
+void attention(Run &r, const sf_model_cfg &m, const void *q, const void *kc, const void *vc, const int32_t *kv_len,
+               void *out, float *part_o, float *part_ml, int B, int n_q, int cap, int mode, int len_upper) {
+  if (r.st != SF_OK) return;
+  AttnArgs a{};
+  a.q = q; a.kc = kc; a.vc = vc; a.kv_len = kv_len; a.out = out; a.part_o = part_o; a.part_ml = part_ml;
+  a.B = B; a.n_q = n_q; a.Hq = m.n_q_heads; a.Hkv = m.n_kv_heads; a.hd = m.head_dim; a.cap = cap; a.mode = mode;
+  a.len_upper = len_upper;
+  a.chunk_tiles = attn_chunk_tiles(len_upper, n_q);
+  const int n_tiles = (len_upper + n_q + TK - 1) / TK;
+  a.n_chunks = (n_tiles + a.chunk_tiles - 1) / a.chunk_tiles;
+  r.ok(m.dtype == SF_BF16 ? launch_attention_bf16(a, r.s) : launch_attention_f32(a, r.s));
+}
+
+size_t kv_layer_bytes(const sf_model_cfg &m, int B, int cap) {
+  return (size_t)B * m.n_kv_heads * cap * m.head_dim * esize(m.dtype);
+}
+
+sf_status check_state(const sf_ctx *c, const sf_state *st, int k, bool need_draft) {
+  if (!c || !st) return SF_EINVAL;
+  if (!c->bound) return SF_ESTATE;
+  if (need_draft && !c->has_draft) return SF_ESTATE;
+  if (k < 0 || k > c->max_k || st->B < 1 || st->B > c->max_B) return SF_EINVAL;
+  if (st->cap < TK || st->cap % TK) return SF_EINVAL;
+  if (!st->kv_len || !st->pending || !st->hooks || !st->n_new || !st->cu_new || !st->workspace) return SF_EINVAL;
+  if (!st->tk || !st->tv) return SF_EINVAL;
+  if (need_draft && (!st->dk || !st->dv)) return SF_EINVAL;
+  if (((uintptr_t)st->workspace) % ALIGN) return SF_EINVAL;
+  if (st->workspace_bytes < plan(c, st->B, k, st->cap).total) return SF_ECAPACITY;
+  return SF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+sf_status sf_create(const sf_model_cfg *t, const sf_model_cfg *d, int32_t max_B, int32_t max_k, sf_ctx **out) {
+  if (!t || !d || !out) return SF_EINVAL;
+  if (max_B < 1 || max_B > 4096 || max_k < 0 || max_k > 15) return SF_EINVAL;
+  if (t->n_layers < 1 || d->n_layers != 1 || !same_shape(*t, *d)) return SF_EINVAL;
+  if (t->d_model < 8 || t->n_q_heads < 1 || t->n_kv_heads < 1 || t->head_dim < 8 || t->d_ffn < 8 || t->vocab < 1)
+    return SF_EINVAL;
+  if (t->n_q_heads % t->n_kv_heads) return SF_EINVAL;
+  if (t->dtype != SF_BF16 && t->dtype != SF_F32) return SF_EINVAL;
+  if (!(t->rms_eps >= 0.f) || !(t->rope_theta > 1.f)) return SF_EINVAL;
+  if (t->d_model % 8 || t->d_ffn % 8 || (t->n_q_heads * t->head_dim) % 8) return SF_EUNSUPPORTED;
+  if (t->dtype == SF_BF16 && t->head_dim != 64 && t->head_dim != 128) return SF_EUNSUPPORTED;
+  if (t->dtype == SF_F32 && (t->head_dim % 8 || t->head_dim > 256)) return SF_EUNSUPPORTED;
+  sf_status s = check_attn_shape(*t, max_k + 1);
+  if (s != SF_OK) return s;
+  sf_ctx *c = new (std::nothrow) sf_ctx();
+  if (!c) return SF_EINVAL;
+  c->tc = *t; c->dc = *d; c->max_B = max_B; c->max_k = max_k;
+  c->bound = false; c->has_draft = false; c->hip_err = 0;
+  *out = c;
+  return SF_OK;
+}
+
+sf_status sf_destroy(sf_ctx *c) {
+  if (!c) return SF_EINVAL;
+  delete c;
+  return SF_OK;
+}
+
+size_t sf_workspace_bytes(const sf_ctx *c, int32_t B, int32_t k, int32_t cap) {
+  if (!c || B < 1 || B > c->max_B || k < 0 || k > c->max_k || cap < TK || cap % TK) return 0;
+  return plan(c, B, k, cap).total;
+}
+
+size_t sf_kv_cache_bytes(const sf_ctx *c, int32_t which, int32_t B, int32_t cap) {
+  if (!c || B < 1 || cap < TK || cap % TK || (which != 0 && which != 1)) return 0;
+  return kv_layer_bytes(c->tc, B, cap) * (which == 0 ? c->tc.n_layers : 1);
+}
+
+sf_status sf_bind(sf_ctx *c, const sf_target_weights *t, const sf_draft_weights *d) {
+  if (!c || !t) return SF_EINVAL;
+  if (!t->embed || !t->lm_head || !t->final_norm || !t->attn_norm || !t->wqkv || !t->wo || !t->ffn_norm ||
+      !t->w_gate_up || !t->w_down)
+    return SF_EINVAL;
+  const int L = c->tc.n_layers;
+  for (int l = 0; l < L; ++l)
+    if (!t->attn_norm[l] || !t->wqkv[l] || !t->wo[l] || !t->ffn_norm[l] || !t->w_gate_up[l] || !t->w_down[l])
+      return SF_EINVAL;
+  if (d) {
+    const void *const *p = reinterpret_cast<const void *const *>(d);
+    for (size_t i = 0; i < sizeof(sf_draft_weights) / sizeof(void *); ++i)
+      if (!p[i]) return SF_EINVAL;
+  }
+  c->tw = *t;
+  c->attn_norm.assign(t->attn_norm, t->attn_norm + L);
+  c->wqkv.assign(t->wqkv, t->wqkv + L);
+  c->wo.assign(t->wo, t->wo + L);
+  c->ffn_norm.assign(t->ffn_norm, t->ffn_norm + L);
+  c->w_gate_up.assign(t->w_gate_up, t->w_gate_up + L);
+  c->w_down.assign(t->w_down, t->w_down + L);
+  c->has_draft = d != nullptr;
+  if (d) c->dw = *d;
+  c->bound = true;
+  return SF_OK;
+}
+
+sf_status sf_verify_step(sf_ctx *c, const sf_state *st, int32_t k, const int32_t *draft, int32_t len_upper,
+                         float *logits, void *stream) {
+  sf_status v = check_state(c, st, k, false);
+  if (v != SF_OK) return v;
+  if (!logits || (k > 0 && !draft) || len_upper < 0) return SF_EINVAL;
+  const sf_model_cfg &m = c->tc;
+  const int B = st->B, q = k + 1, M = B * q, cap = st->cap, qm = c->max_k + 1;
+  if ((long)len_upper + q > cap) return SF_ECAPACITY;
+  if ((v = check_attn_shape(m, q)) != SF_OK) return v;
+  const Arena A = plan(c, B, k, cap);
+  char *ws = (char *)st->workspace;
+  void *h = ws + A.h, *a = ws + A.a, *qkv = ws + A.qkv, *qr = ws + A.qr, *ao = ws + A.ao, *act = ws + A.act;
+  float *gu = (float *)(ws + A.gu);
+  const int d = m.d_model, F = m.d_ffn, L = m.n_layers;
+  const int nq = m.n_q_heads * m.head_dim, nkv = m.n_kv_heads * m.head_dim;
+  Run r{c, (hipStream_t)stream};
+  r.ok(launch_embed(c->tw.embed, st->pending, draft, h, st->hooks, B, k, qm, d, m.vocab, m.dtype, r.s));
+  RopeArgs ra{};
+  ra.qkv = qkv; ra.q_out = qr; ra.kv_len = st->kv_len; ra.n_new = nullptr; ra.table = (float2 *)(ws + A.table);
+  ra.B = B; ra.n_q = q; ra.Hq = m.n_q_heads; ra.Hkv = m.n_kv_heads; ra.hd = m.head_dim; ra.cap = cap;
+  ra.kv_only = 0; ra.pos_mode = 0; ra.theta = m.rope_theta;
+  if (r.st == SF_OK) r.ok(launch_rope_table(ra, r.s));
+  const int hook_layer[4] = {0, L / 2, L - 1, L};
+  const size_t lb = kv_layer_bytes(m, B, cap);
+  for (int l = 0; l <= L && r.st == SF_OK; ++l) {
+    for (int g = 1; g < 4; ++g)
+      if (hook_layer[g] == l && r.st == SF_OK) r.ok(launch_hook_copy(h, st->hooks, B, q, qm, d, g, m.dtype, r.s));
+    if (l == L) break;
+    void *kc = (char *)st->tk + l * lb, *vc = (char *)st->tv + l * lb;
+    norm(r, m, h, c->attn_norm[l], a, M);
+    gemm(r, m.dtype, a, c->wqkv[l], nullptr, nullptr, qkv, M, nq + 2 * nkv, d, 0);
+    ra.kc = kc; ra.vc = vc;
+    if (r.st == SF_OK) r.ok(launch_rope_kv(ra, m.dtype, r.s));
+    attention(r, m, qr, kc, vc, st->kv_len, ao, (float *)(ws + A.part_o), (float *)(ws + A.part_ml), B, q, cap,
+              SF_MASK_CAUSAL, len_upper);
+    gemm(r, m.dtype, ao, c->wo[l], nullptr, h, h, M, d, nq, 0);
+    norm(r, m, h, c->ffn_norm[l], a, M);
+    gemm(r, m.dtype, a, c->w_gate_up[l], nullptr, nullptr, gu, M, 2 * F, d, 1);
+    if (r.st == SF_OK) r.ok(launch_silu_mul(gu, act, M, F, m.dtype, r.s));
+    gemm(r, m.dtype, act, c->w_down[l], nullptr, h, h, M, d, F, 0);
+  }
+  norm(r, m, h, c->tw.final_norm, a, M);
+  gemm(r, m.dtype, a, c->tw.lm_head, nullptr, nullptr, logits, M, m.vocab, d, 1);
+  return r.st;
+}
+
+sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, int32_t len_upper,
+                        int32_t *draft_tokens, void *stream) {
+  sf_status v = check_state(c, st, k, true);
+  if (v != SF_OK) return v;
+  if (k == 0) return SF_OK;
+  if (!draft_tokens || len_upper < 0 || (mask != SF_MASK_CAUSAL && mask != SF_MASK_BIDIR)) return SF_EINVAL;
+  const sf_model_cfg &m = c->dc;
+  const int B = st->B, cap = st->cap, qm = c->max_k + 1, Mh = B * qm, Ms = B * k;
+  if ((long)len_upper + k > cap) return SF_ECAPACITY;
+  if ((v = check_attn_shape(m, k)) != SF_OK) return v;
+  const Arena A = plan(c, B, k, cap);
+  char *ws = (char *)st->workspace;
+  void *a = ws + A.a, *qkv = ws + A.qkv, *qr = ws + A.qr, *ao = ws + A.ao, *act = ws + A.act;
+  void *f4 = ws + A.f4, *x = ws + A.x, *kvc = ws + A.kvc, *xl = ws + A.xl, *s0 = ws + A.s0;
+  float *gu = (float *)(ws + A.gu), *dlogits = (float *)(ws + A.dlogits);
+  const int d = m.d_model, F = m.d_ffn;
+  const int nq = m.n_q_heads * m.head_dim, nkv = m.n_kv_heads * m.head_dim;
+  const size_t es = esize(m.dtype);
+  const sf_draft_weights &w = c->dw;
+  Run r{c, (hipStream_t)stream};
+  // context rows: Grouped RMSNorm -> W_D -> K,V of the draft attention layer at the rows' positions
+  norm(r, m, st->hooks, w.group_norm, f4, Mh * 4, 4, 1, qm, qm, nullptr);
+  gemm(r, m.dtype, f4, w.w_ds, nullptr, nullptr, x, Mh, d, 4 * d, 0);
+  norm(r, m, x, w.attn_norm, a, Mh);
+  gemm(r, m.dtype, a, (const char *)w.wqkv + (size_t)nq * d * es, nullptr, nullptr, kvc, Mh, 2 * nkv, d, 0);
+  RopeArgs ra{};
+  ra.qkv = kvc; ra.q_out = nullptr; ra.kc = st->dk; ra.vc = st->dv; ra.kv_len = st->kv_len; ra.n_new = st->n_new;
+  ra.table = (float2 *)(ws + A.table);
+  ra.B = B; ra.n_q = qm; ra.Hq = m.n_q_heads; ra.Hkv = m.n_kv_heads; ra.hd = m.head_dim; ra.cap = cap;
+  ra.kv_only = 1; ra.pos_mode = 1; ra.theta = m.rope_theta;
+  if (r.st == SF_OK) r.ok(launch_rope_table(ra, r.s));
+  if (r.st == SF_OK) r.ok(launch_rope_kv(ra, m.dtype, r.s));
+  // positional FFN on the newest committed row -> k slot states
+  norm(r, m, x, w.pos_norm, xl, B, 1, 2, qm, qm, st->n_new);
+  gemm(r, m.dtype, xl, w.w_pos, w.b_pos, nullptr, s0, B, k * d, d, 0);
+  // one attention + SwiGLU layer over the slots
+  norm(r, m, s0, w.attn_norm, a, Ms);
+  gemm(r, m.dtype, a, w.wqkv, nullptr, nullptr, qkv, Ms, nq + 2 * nkv, d, 0);
+  ra.qkv = qkv; ra.q_out = qr; ra.n_new = nullptr; ra.n_q = k; ra.kv_only = 0; ra.pos_mode = 0;
+  if (r.st == SF_OK) r.ok(launch_rope_table(ra, r.s));
+  if (r.st == SF_OK) r.ok(launch_rope_kv(ra, m.dtype, r.s));
+  attention(r, m, qr, st->dk, st->dv, st->kv_len, ao, (float *)(ws + A.part_o), (float *)(ws + A.part_ml), B, k,
+            cap, mask, len_upper);
+  gemm(r, m.dtype, ao, w.wo, nullptr, s0, s0, Ms, d, nq, 0);
+  norm(r, m, s0, w.ffn_norm, a, Ms);
+  gemm(r, m.dtype, a, w.w_gate_up, nullptr, nullptr, gu, Ms, 2 * F, d, 1);
+  if (r.st == SF_OK) r.ok(launch_silu_mul(gu, act, Ms, F, m.dtype, r.s));
+  gemm(r, m.dtype, act, w.w_down, nullptr, s0, s0, Ms, d, F, 0);
+  norm(r, m, s0, w.out_norm, a, Ms);
+  gemm(r, m.dtype, a, c->tw.lm_head, nullptr, nullptr, dlogits, Ms, m.vocab, d, 1);
+  if (r.st == SF_OK)
+    r.ok(launch_argmax_partial(dlogits, Ms, m.vocab, (float *)(ws + A.pmax), (int32_t *)(ws + A.pidx), r.s));
+  if (r.st == SF_OK)
+    r.ok(launch_argmax_final((float *)(ws + A.pmax), (int32_t *)(ws + A.pidx), Ms, draft_tokens, r.s));
+  return r.st;
+}
+
+sf_status sf_accept_commit(sf_ctx *c, const sf_state *st, int32_t k, const int32_t *draft, const float *logits,
+                           const int32_t *force_len, int32_t *accept_len, int32_t *out_tokens, void *stream) {
+  sf_status v = check_state(c, st, k, false);
+  if (v != SF_OK) return v;
+  if (!logits || !accept_len || !out_tokens || (k > 0 && !draft && !force_len)) return SF_EINVAL;
+  const Arena A = plan(c, st->B, k, st->cap);
+  char *ws = (char *)st->workspace;
+  Run r{c, (hipStream_t)stream};
+  const int M = st->B * (k + 1);
+  r.ok(launch_argmax_partial(logits, M, c->tc.vocab, (float *)(ws + A.pmax), (int32_t *)(ws + A.pidx), r.s));
+  AcceptArgs a{(float *)(ws + A.pmax), (int32_t *)(ws + A.pidx), draft, force_len, accept_len, out_tokens,
+               st->kv_len, st->pending, st->n_new, st->cu_new, st->B, k};
+  if (r.st == SF_OK) r.ok(launch_accept(a, r.s));
+  return r.st;
+}
+
+sf_status sf_kv_import(const sf_ctx *c, const void *plain, void *tiled, int32_t is_v, int32_t B, int32_t cap,
+                       void *stream) {
+  if (!c || !plain || !tiled || B < 1 || cap < TK || cap % TK) return SF_EINVAL;
+  hipError_t e = launch_kv_convert(plain, tiled, is_v, 1, B, c->tc.n_kv_heads, cap, c->tc.head_dim, c->tc.dtype,
+                                   (hipStream_t)stream);
+  if (e != hipSuccess) { c->hip_err = (int)e; return SF_EHIP; }
+  return SF_OK;
+}
+
+sf_status sf_kv_export(const sf_ctx *c, const void *tiled, void *plain, int32_t is_v, int32_t B, int32_t cap,
+                       void *stream) {
+  if (!c || !plain || !tiled || B < 1 || cap < TK || cap % TK) return SF_EINVAL;
+  hipError_t e = launch_kv_convert(tiled, plain, is_v, 0, B, c->tc.n_kv_heads, cap, c->tc.head_dim, c->tc.dtype,
+                                   (hipStream_t)stream);
+  if (e != hipSuccess) { c->hip_err = (int)e; return SF_EHIP; }
+  return SF_OK;
+}
+
+size_t sf_attention_workspace_bytes(const sf_ctx *c, int32_t B, int32_t n_q, int32_t len_upper) {
+  if (!c || B < 1 || n_q < 1 || len_upper < 0 || c->tc.dtype != SF_BF16) return 0;
+  return attn_workspace_bytes(B, c->tc.n_kv_heads, c->tc.head_dim, c->tc.n_q_heads / c->tc.n_kv_heads, n_q,
+                              len_upper);
+}
+
+sf_status sf_op_attention(const sf_ctx *c, const void *q, const void *kc, const void *vc, const int32_t *kv_len,
+                          int32_t B, int32_t n_q, int32_t cap, int32_t mask, int32_t len_upper, void *out,
+                          void *workspace, size_t workspace_bytes, void *stream) {
+  if (!c || !q || !kc || !vc || !kv_len || !out) return SF_EINVAL;
+  if (B < 1 || n_q < 1 || cap < TK || cap % TK || len_upper < 0) return SF_EINVAL;
+  if (mask != SF_MASK_CAUSAL && mask != SF_MASK_BIDIR) return SF_EINVAL;
+  if ((long)len_upper + n_q > cap) return SF_ECAPACITY;
+  const sf_model_cfg &m = c->tc;
+  sf_status v = check_attn_shape(m, n_q);
+  if (v != SF_OK) return v;
+  const size_t need = sf_attention_workspace_bytes(c, B, n_q, len_upper);
+  if (need && (!workspace || workspace_bytes < need || ((uintptr_t)workspace) % ALIGN)) return SF_ECAPACITY;
+  const size_t rows = need / ((m.head_dim + 2) * sizeof(float));
+  float *part_o = (float *)workspace, *part_ml = part_o ? part_o + rows * m.head_dim : nullptr;
+  Run r{c, (hipStream_t)stream};
+  attention(r, m, q, kc, vc, kv_len, out, part_o, part_ml, B, n_q, cap, mask, len_upper);
+  return r.st;
+}
+
+sf_status sf_op_linear(const sf_ctx *c, const void *x, const void *w, const void *bias, const void *residual,
+                       void *y, int32_t M, int32_t N, int32_t K, int32_t out_f32, void *stream) {
+  if (!c || !x || !w || !y || M < 1 || N < 1 || K < 1) return SF_EINVAL;
+  if (K % 8 || N % 8) return SF_EUNSUPPORTED;
+  if (((uintptr_t)x | (uintptr_t)w) % 16) return SF_EINVAL;
+  Run r{c, (hipStream_t)stream};
+  gemm(r, c->tc.dtype, x, w, bias, residual, y, M, N, K, out_f32);
+  return r.st;
+}
+
+sf_status sf_op_rmsnorm(const sf_ctx *c, const void *x, const void *gain, void *y, int32_t M, int32_t d,
+                        int32_t n_gain, void *stream) {
+  if (!c || !x || !gain || !y || M < 1 || d < 1 || n_gain < 1) return SF_EINVAL;
+  NormArgs n{x, gain, y, M, d, n_gain, c->tc.rms_eps, 0, 1, 1, nullptr};
+  Run r{c, (hipStream_t)stream};
+  r.ok(launch_rmsnorm(n, c->tc.dtype, r.s));
+  return r.st;
+}
+
+sf_status sf_op_rope_kv_append(const sf_ctx *c, const void *qkv, const int32_t *kv_len, int32_t B, int32_t n_q,
+                               int32_t cap, void *q_out, void *kc, void *vc, void *workspace, size_t workspace_bytes,
+                               void *stream) {
+  if (!c || !qkv || !kv_len || !q_out || !kc || !vc || !workspace) return SF_EINVAL;
+  if (B < 1 || n_q < 1 || cap < TK || cap % TK) return SF_EINVAL;
+  const sf_model_cfg &m = c->tc;
+  if (workspace_bytes < (size_t)B * n_q * (m.head_dim / 2) * sizeof(float2)) return SF_ECAPACITY;
+  RopeArgs ra{};
+  ra.qkv = qkv; ra.q_out = q_out; ra.kc = kc; ra.vc = vc; ra.kv_len = kv_len; ra.table = (float2 *)workspace;
+  ra.B = B; ra.n_q = n_q; ra.Hq = m.n_q_heads; ra.Hkv = m.n_kv_heads; ra.hd = m.head_dim; ra.cap = cap;
+  ra.theta = m.rope_theta;
+  Run r{c, (hipStream_t)stream};
+  r.ok(launch_rope_table(ra, r.s));
+  if (r.st == SF_OK) r.ok(launch_rope_kv(ra, m.dtype, r.s));
+  return r.st;
+}
+
+sf_status sf_op_silu_mul(const sf_ctx *c, const float *gu, void *act, int32_t M, int32_t F, void *stream) {
+  if (!c || !gu || !act || M < 1 || F < 1) return SF_EINVAL;
+  Run r{c, (hipStream_t)stream};
+  r.ok(launch_silu_mul(gu, act, M, F, c->tc.dtype, r.s));
+  return r.st;
+}
+
+size_t sf_argmax_workspace_bytes(int32_t M) {
+  return M < 1 ? 0 : up((size_t)M * ARGMAX_SEGS * sizeof(float)) + up((size_t)M * ARGMAX_SEGS * sizeof(int32_t));
+}
+
+sf_status sf_op_argmax(const sf_ctx *c, const float *logits, int32_t M, int32_t V, int32_t *ids, void *workspace,
+                       size_t workspace_bytes, void *stream) {
+  if (!c || !logits || !ids || !workspace || M < 1 || V < 1) return SF_EINVAL;
+  if (workspace_bytes < sf_argmax_workspace_bytes(M) || ((uintptr_t)workspace) % ALIGN) return SF_ECAPACITY;
+  float *pmax = (float *)workspace;
+  int32_t *pidx = (int32_t *)((char *)workspace + up((size_t)M * ARGMAX_SEGS * sizeof(float)));
+  Run r{c, (hipStream_t)stream};
+  r.ok(launch_argmax_partial(logits, M, V, pmax, pidx, r.s));
+  if (r.st == SF_OK) r.ok(launch_argmax_final(pmax, pidx, M, ids, r.s));
+  return r.st;
+}
+
+const char *sf_strerror(sf_status s) {
+  switch (s) {
+    case SF_OK: return "ok";
+    case SF_EINVAL: return "invalid argument";
+    case SF_ECAPACITY: return "capacity exceeded (cache or workspace too small)";
+    case SF_ESTATE: return "call order: weights not bound";
+    case SF_EHIP: return "HIP error";
+    case SF_EUNSUPPORTED: return "shape not supported by the kernels";
+  }
+  return "unknown status";
+}
+
+int sf_last_hip_error(const sf_ctx *c) { return c ? c->hip_err : 0; }
+const char *sf_version(void) { return "specformer-mi355x 0.1 (gfx950)"; }
+
+}  // extern "C"

@@ -1,0 +1,244 @@
+// Bandwidth-trivial row kernels of the SpecFormer step for gfx950: RMSNorm / Grouped RMSNorm,
+// rotary embedding + K/V append into the tiled caches, SwiGLU gating, embedding gather,
+// hook capture, cache layout conversion.  All statistics and rotations in fp32.
+#include "sf_internal.h"
+
+namespace sf {
+namespace {
+
+__device__ __forceinline__ float block_sum_256(float v, float *red) {
+  for (int o = 32; o; o >>= 1) v += __shfl_xor(v, o);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  const float t = red[0] + red[1] + red[2] + red[3];
+  __syncthreads();
+  return t;
+}
+
+// One workgroup per output row.  y = gain[r % n_gain] * x / sqrt(mean(x^2) + eps).
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const T *__restrict__ X, const T *__restrict__ gain,
+                                                      T *__restrict__ Y, int d, int n_gain, float eps, int map,
+                                                      int q, int q_max, const int32_t *__restrict__ n_new) {
+  __shared__ float red[4];
+  const int r = blockIdx.x;
+  long in_row = r;
+  bool zero = false;
+  if (map == 1) {  // hooks rows: r = (b*q + i)*4 + g
+    const int g = r & 3, bi = r >> 2, b = bi / q, i = bi % q;
+    in_row = ((long)b * q_max + i) * 4 + g;
+  } else if (map == 2) {  // newest committed row of sequence r
+    const int nn = n_new[r];
+    zero = nn <= 0;
+    in_row = (long)r * q + (zero ? 0 : min(nn, q) - 1);
+  }
+  const T *x = X + in_row * d;
+  const T *gv = gain + (size_t)(r % n_gain) * d;
+  T *y = Y + (size_t)r * d;
+  float ss = 0.f;
+  if (!zero)
+    for (int e = threadIdx.x; e < d; e += 256) {
+      const float v = Elem<T>::ld(x + e);
+      ss += v * v;
+    }
+  ss = block_sum_256(ss, red);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int e = threadIdx.x; e < d; e += 256) {
+    const float v = zero ? 0.f : Elem<T>::ld(x + e);
+    Elem<T>::st(y + e, Elem<T>::ld(gv + e) * (v * inv));
+  }
+}
+
+// cos/sin of pos * theta^(-2i/hd), evaluated in double so that large positions stay exact to fp32.
+__global__ void rope_table_kernel(float2 *__restrict__ table, const int32_t *__restrict__ kv_len,
+                                  const int32_t *__restrict__ n_new, int B, int n_q, int half, int pos_mode,
+                                  double log2_theta) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= B * n_q * half) return;
+  const int i = idx % half, row = idx / half, b = row / n_q, r = row % n_q;
+  const int pos = pos_mode == 0 ? kv_len[b] + r : kv_len[b] - n_new[b] + r;
+  const double inv_freq = exp2(-(double)(2 * i) / (double)(2 * half) * log2_theta);
+  double s, c;
+  sincos((double)pos * inv_freq, &s, &c);
+  table[idx] = make_float2((float)c, (float)s);
+}
+
+// One workgroup per row (b,i).  Rotates q and k (pairs (e, e+hd/2)), writes q to q_out, k and v into
+// the caches at position pos.  bf16: tiled cache; fp32: plain cache.
+template <typename T>
+__global__ __launch_bounds__(256) void rope_kv_kernel(const T *__restrict__ QKV, T *__restrict__ Qo,
+                                                      T *__restrict__ Kc, T *__restrict__ Vc,
+                                                      const int32_t *__restrict__ kv_len,
+                                                      const int32_t *__restrict__ n_new,
+                                                      const float2 *__restrict__ table, int n_q, int Hq, int Hkv,
+                                                      int hd, int cap, int kv_only, int pos_mode) {
+  const int row = blockIdx.x, b = row / n_q, i = row % n_q;
+  const int half = hd >> 1;
+  const int nq_cols = kv_only ? 0 : Hq * hd, nkv = Hkv * hd;
+  const T *src = QKV + (size_t)row * (nq_cols + 2 * nkv);
+  const float2 *tab = table + (size_t)row * half;
+  int pos;
+  bool valid = true;
+  if (pos_mode == 0) pos = kv_len[b] + i;
+  else { const int nn = n_new[b]; pos = kv_len[b] - nn + i; valid = i < nn; }
+  if (pos < 0 || pos >= cap) valid = false;
+  // q: pairs
+  for (int x = threadIdx.x; x < Hq * half && !kv_only; x += 256) {
+    const int hh = x / half, e = x % half;
+    const float2 cs = tab[e];
+    const float a = Elem<T>::ld(src + hh * hd + e), bb = Elem<T>::ld(src + hh * hd + e + half);
+    Elem<T>::st(Qo + (size_t)row * nq_cols + hh * hd + e, a * cs.x - bb * cs.y);
+    Elem<T>::st(Qo + (size_t)row * nq_cols + hh * hd + e + half, bb * cs.x + a * cs.y);
+  }
+  if (!valid) return;
+  const size_t tile = pos / TK;
+  const int a_in = pos % TK;
+  for (int x = threadIdx.x; x < Hkv * half; x += 256) {
+    const int g = x / half, e = x % half;
+    const float2 cs = tab[e];
+    const float a = Elem<T>::ld(src + nq_cols + g * hd + e), bb = Elem<T>::ld(src + nq_cols + g * hd + e + half);
+    const float k0 = a * cs.x - bb * cs.y, k1 = bb * cs.x + a * cs.y;
+    const float v0 = Elem<T>::ld(src + nq_cols + nkv + g * hd + e);
+    const float v1 = Elem<T>::ld(src + nq_cols + nkv + g * hd + e + half);
+    if (sizeof(T) == 2) {
+      const size_t base = (((size_t)b * Hkv + g) * (cap / TK) + tile) * (size_t)(TK * hd);
+      Elem<T>::st(Kc + base + k_tile_off(a_in, e), k0);
+      Elem<T>::st(Kc + base + k_tile_off(a_in, e + half), k1);
+      Elem<T>::st(Vc + base + v_tile_off(a_in, e, hd), v0);
+      Elem<T>::st(Vc + base + v_tile_off(a_in, e + half, hd), v1);
+    } else {
+      const size_t base = (((size_t)b * Hkv + g) * cap + pos) * (size_t)hd;
+      Elem<T>::st(Kc + base + e, k0);
+      Elem<T>::st(Kc + base + e + half, k1);
+      Elem<T>::st(Vc + base + e, v0);
+      Elem<T>::st(Vc + base + e + half, v1);
+    }
+  }
+}
+
+template <typename T>
+__global__ void silu_mul_kernel(const float *__restrict__ gu, T *__restrict__ act, int M, int F) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)M * F) return;
+  const size_t m = idx / F, f = idx % F;
+  const float g = gu[m * 2 * F + f], u = gu[m * 2 * F + F + f];
+  Elem<T>::st(act + idx, g / (1.0f + expf(-g)) * u);
+}
+
+// h[row] = embed[token(row)], also stored as hooked state 0.  Out-of-range ids read row 0.
+template <typename T>
+__global__ __launch_bounds__(256) void embed_kernel(const T *__restrict__ E, const int32_t *__restrict__ pending,
+                                                    const int32_t *__restrict__ draft, T *__restrict__ H,
+                                                    T *__restrict__ hooks, int k, int q_max, int d, int vocab) {
+  const int row = blockIdx.x, q = k + 1, b = row / q, i = row % q;
+  int tok = i == 0 ? pending[b] : draft[b * k + i - 1];
+  if (tok < 0 || tok >= vocab) tok = 0;
+  const T *src = E + (size_t)tok * d;
+  T *h = H + (size_t)row * d;
+  T *hk = hooks + (((size_t)b * q_max + i) * 4 + 0) * d;
+  for (int e = threadIdx.x; e < d; e += 256) { const T v = src[e]; h[e] = v; hk[e] = v; }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void hook_copy_kernel(const T *__restrict__ H, T *__restrict__ hooks, int q,
+                                                        int q_max, int d, int group) {
+  const int row = blockIdx.x, b = row / q, i = row % q;
+  const T *h = H + (size_t)row * d;
+  T *hk = hooks + (((size_t)b * q_max + i) * 4 + group) * d;
+  for (int e = threadIdx.x; e < d; e += 256) hk[e] = h[e];
+}
+
+// plain [B][Hkv][cap][hd] <-> tiled (bf16) / plain (fp32: straight copy)
+template <typename T>
+__global__ void kv_convert_kernel(const T *__restrict__ src, T *__restrict__ dst, int is_v, int to_tiled,
+                                  size_t n, int cap, int hd) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n) return;
+  size_t t_idx = idx;
+  if (sizeof(T) == 2) {
+    const int c = idx % hd;
+    const size_t pos_all = idx / hd;  // (b*Hkv+g)*cap + pos
+    const int pos = pos_all % cap;
+    const size_t slab = pos_all / cap;
+    const size_t base = (slab * (cap / TK) + pos / TK) * (size_t)(TK * hd);
+    t_idx = base + (is_v ? v_tile_off(pos % TK, c, hd) : k_tile_off(pos % TK, c));
+  }
+  if (to_tiled) dst[t_idx] = src[idx];
+  else dst[idx] = src[t_idx];
+}
+
+template <typename T>
+hipError_t rmsnorm_t(const NormArgs &a, hipStream_t s) {
+  rmsnorm_kernel<T><<<a.M, 256, 0, s>>>((const T *)a.x, (const T *)a.gain, (T *)a.y, a.d, a.n_gain, a.eps, a.map,
+                                        a.q, a.q_max, a.n_new);
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t rope_kv_t(const RopeArgs &a, hipStream_t s) {
+  const int M = a.B * a.n_q;
+  rope_kv_kernel<T><<<M, 256, 0, s>>>((const T *)a.qkv, (T *)a.q_out, (T *)a.kc, (T *)a.vc, a.kv_len, a.n_new,
+                                      a.table, a.n_q, a.Hq, a.Hkv, a.hd, a.cap, a.kv_only, a.pos_mode);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_rmsnorm(const NormArgs &a, int dtype, hipStream_t s) {
+  return dtype == SF_BF16 ? rmsnorm_t<bf16_t>(a, s) : rmsnorm_t<float>(a, s);
+}
+
+hipError_t launch_rope_table(const RopeArgs &a, hipStream_t s) {
+  const int half = a.hd / 2;
+  const int n = a.B * a.n_q * half;
+  rope_table_kernel<<<(n + 255) / 256, 256, 0, s>>>(a.table, a.kv_len, a.n_new, a.B, a.n_q, half, a.pos_mode,
+                                                    log2((double)a.theta));
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_kv(const RopeArgs &a, int dtype, hipStream_t s) {
+  return dtype == SF_BF16 ? rope_kv_t<bf16_t>(a, s) : rope_kv_t<float>(a, s);
+}
+
+hipError_t launch_silu_mul(const float *gu, void *act, int M, int F, int dtype, hipStream_t s) {
+  const size_t n = (size_t)M * F;
+  const unsigned blocks = (unsigned)((n + 255) / 256);
+  if (dtype == SF_BF16) silu_mul_kernel<bf16_t><<<blocks, 256, 0, s>>>(gu, (bf16_t *)act, M, F);
+  else silu_mul_kernel<float><<<blocks, 256, 0, s>>>(gu, (float *)act, M, F);
+  return hipGetLastError();
+}
+
+hipError_t launch_embed(const void *embed, const int32_t *pending, const int32_t *draft, void *h, void *hooks,
+                        int B, int k, int q_max, int d, int vocab, int dtype, hipStream_t s) {
+  const int M = B * (k + 1);
+  if (dtype == SF_BF16)
+    embed_kernel<bf16_t><<<M, 256, 0, s>>>((const bf16_t *)embed, pending, draft, (bf16_t *)h, (bf16_t *)hooks, k,
+                                           q_max, d, vocab);
+  else
+    embed_kernel<float><<<M, 256, 0, s>>>((const float *)embed, pending, draft, (float *)h, (float *)hooks, k,
+                                          q_max, d, vocab);
+  return hipGetLastError();
+}
+
+hipError_t launch_hook_copy(const void *h, void *hooks, int B, int q, int q_max, int d, int group, int dtype,
+                            hipStream_t s) {
+  if (dtype == SF_BF16)
+    hook_copy_kernel<bf16_t><<<B * q, 256, 0, s>>>((const bf16_t *)h, (bf16_t *)hooks, q, q_max, d, group);
+  else
+    hook_copy_kernel<float><<<B * q, 256, 0, s>>>((const float *)h, (float *)hooks, q, q_max, d, group);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_convert(const void *src, void *dst, int is_v, int to_tiled, int B, int Hkv, int cap, int hd,
+                             int dtype, hipStream_t s) {
+  const size_t n = (size_t)B * Hkv * cap * hd;
+  const unsigned blocks = (unsigned)((n + 255) / 256);
+  if (dtype == SF_BF16)
+    kv_convert_kernel<bf16_t><<<blocks, 256, 0, s>>>((const bf16_t *)src, (bf16_t *)dst, is_v, to_tiled, n, cap, hd);
+  else
+    kv_convert_kernel<float><<<blocks, 256, 0, s>>>((const float *)src, (float *)dst, is_v, to_tiled, n, cap, hd);
+  return hipGetLastError();
+}
+
+}  // namespace sf

@@ -1,0 +1,143 @@
+// Internal declarations shared by the HIP translation units of libspecformer (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/specformer.h"
+
+namespace sf {
+
+typedef uint16_t bf16_t;  // raw bf16 bits in memory
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ bf16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack2bf(float lo, float hi) {
+  return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<bf16_t> {
+  static __device__ __forceinline__ float ld(const bf16_t *p) { return bf2f(*p); }
+  static __device__ __forceinline__ void st(bf16_t *p, float v) { *p = f2bf(v); }
+};
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float ld(const float *p) { return *p; }
+  static __device__ __forceinline__ void st(float *p, float v) { *p = v; }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Tiled K/V cache (bf16).  A tile holds TK = 32 consecutive positions of one (sequence, kv head)
+// as one contiguous blob of 32*HD elements, ordered so that a wavefront's MFMA operand loads are
+// `blob[i*64 + lane]` in 16-byte units.
+//
+// 32x32x16 MFMA accumulator layout: lane l, register v holds row c_row(v, l/32), column l%32.
+__host__ __device__ constexpr int c_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
+
+constexpr int TK = 32;
+
+// K tile: element (key a in [0,32), feature c) -> element offset inside the blob.
+// 16-byte unit index = (c/8)*32 + a : k-step s of the QK^T product reads units [s*64, s*64+64).
+__host__ __device__ constexpr int k_tile_off(int a, int c) { return ((c >> 3) * 32 + a) * 8 + (c & 7); }
+
+// V tile: element (key a, feature c) -> element offset.  The P.V product runs as O^T = V^T.P^T with
+// the keys as the MFMA reduction dimension, 16 keys per MFMA (u = a/16).  Inside a 16-key group,
+// lane half h and operand element e hold key 16u + 8*(e/4) + 4h + e%4 (the accumulator layout of the
+// preceding S^T = K.Q^T product, so P needs no shuffle).  16-byte unit = ((u*NT + c/32)*2 + h)*32 + c%32.
+__host__ __device__ constexpr int v_tile_off(int a, int c, int hd) {
+  int u = a >> 4, a16 = a & 15;
+  int h = (a16 >> 2) & 1, e = ((a16 >> 3) << 2) | (a16 & 3);
+  return ((((u * (hd >> 5) + (c >> 5)) * 2 + h) * 32) + (c & 31)) * 8 + e;
+}
+
+// fp32 mode keeps the plain layout [B][Hkv][cap][hd].
+
+struct Launch {
+  hipStream_t stream;
+  int hip_err;  // first failing hipError_t, 0 if none
+};
+
+// ---- kernel launchers (defined in the .hip files) ---------------------------------------------
+struct AttnArgs {
+  const void *q;
+  const void *kc, *vc;
+  const int32_t *kv_len;
+  void *out;
+  float *part_o;   // [B][Hkv][n_chunks][64][HD]
+  float *part_ml;  // [B][Hkv][n_chunks][64][2]
+  int B, n_q, Hq, Hkv, hd, cap, mode, len_upper;
+  int chunk_tiles;  // tiles of 32 keys per workgroup chunk
+  int n_chunks;     // grid.x
+};
+int attn_chunk_tiles(int len_upper, int n_q);
+size_t attn_workspace_bytes(int B, int Hkv, int hd, int G, int n_q, int len_upper);
+hipError_t launch_attention_bf16(const AttnArgs &a, hipStream_t s);
+hipError_t launch_attention_f32(const AttnArgs &a, hipStream_t s);
+
+struct GemmArgs {
+  const void *x, *w, *bias, *residual;
+  void *y;
+  int M, N, K;
+  int out_f32;
+};
+hipError_t launch_gemm_bf16(const GemmArgs &a, hipStream_t s);
+hipError_t launch_gemm_f32(const GemmArgs &a, hipStream_t s);
+
+// row-mapped RMSNorm: output row r reads input row in_row(r), see elementwise.hip
+struct NormArgs {
+  const void *x, *gain;
+  void *y;
+  int M, d, n_gain;
+  float eps;
+  // input row mapping: 0 identity; 1 hooks rows: r=(b*q+i)*4+g -> ((b*q_max+i)*4+g);
+  // 2 newest committed row of x[B*q][d]: r=b -> b*q + n_new[b]-1 (zero row when n_new[b]==0)
+  int map;
+  int q, q_max;
+  const int32_t *n_new;
+};
+hipError_t launch_rmsnorm(const NormArgs &a, int dtype, hipStream_t s);
+
+struct RopeArgs {
+  const void *qkv;  // [M][(Hq+2Hkv)*hd] or, kv_only, [M][2*Hkv*hd]
+  void *q_out;      // [M][Hq*hd] (ignored when kv_only)
+  void *kc, *vc;
+  const int32_t *kv_len;
+  const int32_t *n_new;  // pos_mode 1
+  float2 *table;         // [M][hd/2] cos,sin scratch
+  int B, n_q, Hq, Hkv, hd, cap;
+  int kv_only;   // rows carry only K,V
+  int pos_mode;  // 0: pos = kv_len[b]+i, all rows valid; 1: pos = kv_len[b]-n_new[b]+i, valid iff i<n_new[b]
+  float theta;
+};
+// fills a.table for the rows' positions; launch_rope_kv then rotates and appends using it
+hipError_t launch_rope_table(const RopeArgs &a, hipStream_t s);
+hipError_t launch_rope_kv(const RopeArgs &a, int dtype, hipStream_t s);
+
+hipError_t launch_silu_mul(const float *gu, void *act, int M, int F, int dtype, hipStream_t s);
+hipError_t launch_embed(const void *embed, const int32_t *pending, const int32_t *draft, void *h, void *hooks,
+                        int B, int k, int q_max, int d, int vocab, int dtype, hipStream_t s);
+hipError_t launch_hook_copy(const void *h, void *hooks, int B, int q, int q_max, int d, int group, int dtype,
+                            hipStream_t s);
+hipError_t launch_kv_convert(const void *src, void *dst, int is_v, int to_tiled, int B, int Hkv, int cap, int hd,
+                             int dtype, hipStream_t s);
+
+constexpr int ARGMAX_SEGS = 16;
+hipError_t launch_argmax_partial(const float *logits, int M, int V, float *pmax, int32_t *pidx, hipStream_t s);
+hipError_t launch_argmax_final(const float *pmax, const int32_t *pidx, int M, int32_t *ids, hipStream_t s);
+struct AcceptArgs {
+  const float *pmax;
+  const int32_t *pidx;
+  const int32_t *draft, *force_len;
+  int32_t *accept_len, *out_tokens, *kv_len, *pending, *n_new, *cu_new;
+  int B, k;
+};
+hipError_t launch_accept(const AcceptArgs &a, hipStream_t s);
+
+}  // namespace sf

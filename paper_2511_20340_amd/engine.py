@@ -1,0 +1,270 @@
+"""Device-buffer owner for libspecformer: allocates weights, caches, state and workspace as PyTorch
+tensors and hands their pointers to the C ABI.  Method names mirror the C entry points; no step
+of the path is computed here (torch is used for memory, streams and host<->device copies only).
+"""
+import ctypes as C
+
+import numpy as np
+import torch
+
+from . import binding as sfb
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Engine:
+    def __init__(self, cfg, B, cap, max_k, device="cuda:0"):
+        """cfg: dict(n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, dtype
+        ('bf16'|'f32'), rope_theta, rms_eps)."""
+        self.lib = sfb.lib()
+        self.cfg = dict(cfg)
+        self.B, self.cap, self.max_k = int(B), int(cap), int(max_k)
+        self.dev = torch.device(device)
+        self.dtype_id = sfb.SF_BF16 if cfg["dtype"] == "bf16" else sfb.SF_F32
+        self.tdtype = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+        self.L, self.d, self.V = cfg["n_layers"], cfg["d_model"], cfg["vocab"]
+        self.Hq, self.Hkv, self.hd, self.F = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["d_ffn"]
+
+        def mk(n_layers):
+            return sfb.ModelCfg(n_layers, self.d, self.Hq, self.Hkv, self.hd, self.F, self.V,
+                                float(cfg.get("rope_theta", 10000.0)), float(cfg.get("rms_eps", 1e-6)),
+                                self.dtype_id)
+        self._tc, self._dc = mk(self.L), mk(1)
+        self.ctx = C.c_void_p()
+        sfb.check(self.lib.sf_create(C.byref(self._tc), C.byref(self._dc), self.B, self.max_k, C.byref(self.ctx)),
+                  "sf_create")
+        es = 2 if self.dtype_id == sfb.SF_BF16 else 4
+        tb = self.lib.sf_kv_cache_bytes(self.ctx, 0, self.B, self.cap)
+        db = self.lib.sf_kv_cache_bytes(self.ctx, 1, self.B, self.cap)
+        assert tb and db
+        z = lambda nbytes: torch.zeros(nbytes // es, dtype=self.tdtype, device=self.dev)
+        self.tk, self.tv, self.dk, self.dv = z(tb), z(tb), z(db), z(db)
+        self.layer_elems = db // es
+        i32 = dict(dtype=torch.int32, device=self.dev)
+        self.kv_len = torch.zeros(self.B, **i32)
+        self.pending = torch.zeros(self.B, **i32)
+        self.n_new = torch.zeros(self.B, **i32)
+        self.cu_new = torch.zeros(self.B + 1, **i32)
+        self.hooks = torch.zeros(self.B, self.max_k + 1, 4, self.d, dtype=self.tdtype, device=self.dev)
+        wb = self.lib.sf_workspace_bytes(self.ctx, self.B, self.max_k, self.cap)
+        assert wb
+        self.workspace = torch.zeros(wb + 256, dtype=torch.uint8, device=self.dev)
+        off = (-self.workspace.data_ptr()) % 256
+        self._ws_ptr = self.workspace.data_ptr() + off
+        self.st = sfb.State(self.B, self.cap, _ptr(self.tk), _ptr(self.tv), _ptr(self.dk), _ptr(self.dv),
+                            _ptr(self.kv_len), _ptr(self.pending), _ptr(self.hooks), _ptr(self.n_new),
+                            _ptr(self.cu_new), C.c_void_p(self._ws_ptr), wb)
+        self.len_upper = 0          # host-side upper bound of max_b kv_len[b]
+        self._keep = []
+
+    def close(self):
+        if self.ctx:
+            self.lib.sf_destroy(self.ctx)
+            self.ctx = C.c_void_p()
+
+    # ---- weights -----------------------------------------------------------------------------
+    def _up(self, a):
+        if isinstance(a, torch.Tensor):
+            t = a.to(device=self.dev, dtype=self.tdtype).contiguous()
+        else:
+            t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.dev).to(self.tdtype).contiguous()
+        self._keep.append(t)
+        return t
+
+    def bind(self, tw, dw=None):
+        """tw / dw: dicts of arrays (numpy float32 or torch) named as in the C structs; a dict that
+        has separate w_gate / w_up gets them stacked into w_gate_up = [gate; up]."""
+        self._keep = []
+        L = self.L
+
+        def gate_up(w, l=None):
+            if "w_gate_up" in w:
+                return self._up(w["w_gate_up"] if l is None else w["w_gate_up"][l])
+            g, u = (w["w_gate"], w["w_up"]) if l is None else (w["w_gate"][l], w["w_up"][l])
+            g, u = (torch.as_tensor(np.asarray(g)) if not isinstance(g, torch.Tensor) else g,
+                    torch.as_tensor(np.asarray(u)) if not isinstance(u, torch.Tensor) else u)
+            return self._up(torch.cat([g, u], 0))
+        T = sfb.TargetWeights()
+        self.w = {}
+        for n in ("embed", "lm_head", "final_norm"):
+            self.w[n] = self._up(tw[n])
+            setattr(T, n, self.w[n].data_ptr())
+        for n in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_down"):
+            self.w[n] = [self._up(tw[n][l]) for l in range(L)]
+        self.w["w_gate_up"] = [gate_up(tw, l) for l in range(L)]
+        for n in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down"):
+            arr = (C.c_void_p * L)(*[t.data_ptr() for t in self.w[n]])
+            self._keep.append(arr)
+            setattr(T, n, arr)
+        D = None
+        if dw is not None:
+            D = sfb.DraftWeights()
+            self.wd = {}
+            for n, _ in sfb.DraftWeights._fields_:
+                self.wd[n] = gate_up(dw) if n == "w_gate_up" else self._up(dw[n])
+                setattr(D, n, self.wd[n].data_ptr())
+        self._T, self._D = T, D
+        sfb.check(self.lib.sf_bind(self.ctx, C.byref(T), C.byref(D) if D is not None else None), "sf_bind")
+
+    # ---- the three steps ---------------------------------------------------------------------
+    def sf_draft_step(self, k, mask=sfb.SF_MASK_BIDIR, draft_out=None):
+        out = draft_out if draft_out is not None else torch.empty(self.B, max(k, 0), dtype=torch.int32, device=self.dev)
+        sfb.check(self.lib.sf_draft_step(self.ctx, C.byref(self.st), k, mask, self.len_upper, _ptr(out), _stream()),
+                  "sf_draft_step")
+        return out
+
+    def sf_verify_step(self, k, draft, logits_out=None):
+        lg = logits_out if logits_out is not None else \
+            torch.empty(self.B, k + 1, self.V, dtype=torch.float32, device=self.dev)
+        sfb.check(self.lib.sf_verify_step(self.ctx, C.byref(self.st), k, _ptr(draft) if k > 0 else None,
+                                          self.len_upper, _ptr(lg), _stream()), "sf_verify_step")
+        return lg
+
+    def sf_accept_commit(self, k, draft, logits, force_len=None, accept_out=None, tokens_out=None):
+        acc = accept_out if accept_out is not None else torch.empty(self.B, dtype=torch.int32, device=self.dev)
+        out = tokens_out if tokens_out is not None else \
+            torch.empty(self.B, k + 1, dtype=torch.int32, device=self.dev)
+        sfb.check(self.lib.sf_accept_commit(self.ctx, C.byref(self.st), k, _ptr(draft) if k > 0 else None,
+                                            _ptr(logits), _ptr(force_len), _ptr(acc), _ptr(out), _stream()),
+                  "sf_accept_commit")
+        self.len_upper = min(self.len_upper + k + 1, self.cap)
+        return acc, out
+
+    # ---- state helpers (plumbing) ------------------------------------------------------------
+    def set_state(self, kv_len=None, pending=None, n_new=None):
+        if kv_len is not None:
+            self.kv_len.copy_(torch.as_tensor(np.asarray(kv_len, dtype=np.int32)))
+            self.len_upper = int(np.max(kv_len))
+        if pending is not None:
+            self.pending.copy_(torch.as_tensor(np.asarray(pending, dtype=np.int32)))
+        if n_new is not None:
+            self.n_new.copy_(torch.as_tensor(np.asarray(n_new, dtype=np.int32)))
+
+    def layer_cache(self, which, layer=0):
+        """Flat view of one layer's slab of 'tk' | 'tv' | 'dk' | 'dv'."""
+        buf = getattr(self, which)
+        return buf[layer * self.layer_elems:(layer + 1) * self.layer_elems]
+
+    def sf_kv_import(self, plain, which, layer=0):
+        """plain: array [B,Hkv,cap,hd] -> tiled slab of cache `which` ('tk','tv','dk','dv')."""
+        t = self._as_dev(plain).reshape(self.B, self.Hkv, self.cap, self.hd).contiguous()
+        sfb.check(self.lib.sf_kv_import(self.ctx, _ptr(t), _ptr(self.layer_cache(which, layer)),
+                                        int(which[1] == "v"), self.B, self.cap, _stream()), "sf_kv_import")
+        torch.cuda.current_stream().synchronize()
+
+    def sf_kv_export(self, which, layer=0):
+        out = torch.empty(self.B, self.Hkv, self.cap, self.hd, dtype=self.tdtype, device=self.dev)
+        sfb.check(self.lib.sf_kv_export(self.ctx, _ptr(self.layer_cache(which, layer)), _ptr(out),
+                                        int(which[1] == "v"), self.B, self.cap, _stream()), "sf_kv_export")
+        return out
+
+    def _as_dev(self, a):
+        if isinstance(a, torch.Tensor):
+            return a.to(device=self.dev, dtype=self.tdtype)
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.dev).to(self.tdtype)
+
+    # ---- single operations -------------------------------------------------------------------
+    def sf_op_attention(self, q, kc, vc, kv_len, n_q, mask, len_upper=None):
+        """q [B,n_q,Hq,hd] device tensor; kc/vc tiled slabs; kv_len int32 device [B]."""
+        B = q.shape[0]
+        if len_upper is None:
+            len_upper = int(kv_len.max().item())
+        need = self.lib.sf_attention_workspace_bytes(self.ctx, B, n_q, len_upper)
+        ws = torch.empty(need + 256, dtype=torch.uint8, device=self.dev)
+        p = ws.data_ptr() + (-ws.data_ptr()) % 256
+        out = torch.empty_like(q)
+        sfb.check(self.lib.sf_op_attention(self.ctx, _ptr(q), _ptr(kc), _ptr(vc), _ptr(kv_len), B, n_q, self.cap,
+                                           mask, len_upper, _ptr(out), C.c_void_p(p), need, _stream()),
+                  "sf_op_attention")
+        self._keep_ws = ws
+        return out
+
+    def sf_op_linear(self, x, w, bias=None, residual=None, out_f32=False):
+        M, K = x.shape
+        N = w.shape[0]
+        y = torch.empty(M, N, dtype=torch.float32 if out_f32 else self.tdtype, device=self.dev)
+        sfb.check(self.lib.sf_op_linear(self.ctx, _ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(y), M, N, K,
+                                        int(out_f32), _stream()), "sf_op_linear")
+        return y
+
+    def sf_op_rmsnorm(self, x, gain, n_gain=1):
+        M, d = x.shape
+        y = torch.empty_like(x)
+        sfb.check(self.lib.sf_op_rmsnorm(self.ctx, _ptr(x), _ptr(gain), _ptr(y), M, d, n_gain, _stream()),
+                  "sf_op_rmsnorm")
+        return y
+
+    def sf_op_rope_kv_append(self, qkv, kv_len, n_q, kc, vc):
+        B = kv_len.shape[0]
+        q_out = torch.empty(B * n_q, self.Hq * self.hd, dtype=self.tdtype, device=self.dev)
+        nb = B * n_q * (self.hd // 2) * 8
+        ws = torch.empty(nb, dtype=torch.uint8, device=self.dev)
+        sfb.check(self.lib.sf_op_rope_kv_append(self.ctx, _ptr(qkv), _ptr(kv_len), B, n_q, self.cap, _ptr(q_out),
+                                                _ptr(kc), _ptr(vc), _ptr(ws), nb, _stream()),
+                  "sf_op_rope_kv_append")
+        self._keep_ws = ws
+        return q_out
+
+    def sf_op_silu_mul(self, gu):
+        M, F2 = gu.shape
+        act = torch.empty(M, F2 // 2, dtype=self.tdtype, device=self.dev)
+        sfb.check(self.lib.sf_op_silu_mul(self.ctx, _ptr(gu), _ptr(act), M, F2 // 2, _stream()), "sf_op_silu_mul")
+        return act
+
+    def sf_op_argmax(self, logits):
+        M, V = logits.shape
+        nb = self.lib.sf_argmax_workspace_bytes(M)
+        ws = torch.empty(nb + 256, dtype=torch.uint8, device=self.dev)
+        p = ws.data_ptr() + (-ws.data_ptr()) % 256
+        ids = torch.empty(M, dtype=torch.int32, device=self.dev)
+        sfb.check(self.lib.sf_op_argmax(self.ctx, _ptr(logits), M, V, _ptr(ids), C.c_void_p(p), nb, _stream()),
+                  "sf_op_argmax")
+        self._keep_ws = ws
+        return ids
+
+    # ---- prefill: chunked verify with forced acceptance --------------------------------------
+    def prefill(self, prompts):
+        """Feeds every prompt through sf_verify_step in blocks of max_k+1 tokens with forced
+        commits, right-aligned so that all sequences finish with the last block, and runs
+        sf_draft_step after every block so the draft cache follows.  Returns the first emitted
+        token of every sequence (device tensor)."""
+        k, q = self.max_k, self.max_k + 1
+        lens = np.array([len(p) for p in prompts], np.int64)
+        nblk = (lens + q - 1) // q
+        total = int(nblk.max())
+        self.set_state(kv_len=np.zeros(self.B, np.int32), pending=np.zeros(self.B, np.int32),
+                       n_new=np.zeros(self.B, np.int32))
+        done = np.zeros(self.B, np.int64)
+        for step in range(total):
+            toks = np.zeros((self.B, q), np.int32)
+            force = np.zeros(self.B, np.int32)
+            nxt = np.zeros(self.B, np.int32)
+            for b, p in enumerate(prompts):
+                if step < total - nblk[b]:
+                    continue                      # this sequence starts later
+                first = lens[b] - (nblk[b] - 1) * q if done[b] == 0 else q   # short block first
+                seg = p[done[b]:done[b] + first]
+                toks[b, :len(seg)] = seg
+                force[b] = len(seg)
+                done[b] += len(seg)
+                nxt[b] = p[done[b]] if done[b] < lens[b] else -1
+            self.pending.copy_(torch.from_numpy(toks[:, 0].copy()))
+            draft = torch.from_numpy(toks[:, 1:].copy()).to(self.dev)
+            fl = torch.from_numpy(force).to(self.dev)
+            lg = self.sf_verify_step(k, draft)
+            self.sf_accept_commit(k, draft, lg, force_len=fl)
+            self.len_upper = int(done.max())
+            if step < total - 1:
+                # pending of a finished block is the next prompt token, not the target's choice
+                pend = self.pending.cpu().numpy()
+                pend[nxt >= 0] = nxt[nxt >= 0]
+                self.pending.copy_(torch.from_numpy(pend))
+            if k > 0 and self._D is not None:
+                self.sf_draft_step(k)
+        return self.pending.clone()

@@ -1,0 +1,104 @@
+"""The C-ABI library loads without a GPU, exports every symbol include/specformer.h declares, and
+its host-side argument checking returns the documented status codes.  No kernel is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2511_20340_amd import binding as sfb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "specformer.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sf_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    L = sfb.lib()
+    names = declared_functions()
+    assert len(names) >= 20
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(sfb.EXPORTS) == names
+    assert b"gfx950" in L.sf_version()
+
+
+def cfg(**kw):
+    base = dict(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, d_ffn=1024, vocab=1024,
+                rope_theta=10000.0, rms_eps=1e-6, dtype=sfb.SF_F32)
+    base.update(kw)
+    return sfb.ModelCfg(*[base[n] for n, _ in sfb.ModelCfg._fields_])
+
+
+def create(t, d, B=4, k=4):
+    ctx = C.c_void_p()
+    return sfb.lib().sf_create(C.byref(t), C.byref(d), B, k, C.byref(ctx)), ctx
+
+
+def test_create_validates_arguments():
+    L = sfb.lib()
+    st, ctx = create(cfg(), cfg(n_layers=1))
+    assert st == sfb.SF_OK and ctx.value
+    assert L.sf_workspace_bytes(ctx, 4, 4, 128) > 0
+    assert L.sf_workspace_bytes(ctx, 5, 4, 128) == 0            # B > max_B
+    assert L.sf_workspace_bytes(ctx, 4, 5, 128) == 0            # k > max_k
+    assert L.sf_workspace_bytes(ctx, 4, 4, 100) == 0            # cap not a multiple of 32
+    assert L.sf_kv_cache_bytes(ctx, 0, 4, 128) == 2 * 4 * 4 * 128 * 64 * 4
+    assert L.sf_kv_cache_bytes(ctx, 1, 4, 128) == 4 * 4 * 128 * 64 * 4
+    assert L.sf_destroy(ctx) == sfb.SF_OK
+    assert create(cfg(), cfg(n_layers=2))[0] == sfb.SF_EINVAL               # draft block is one layer
+    assert create(cfg(), cfg(n_layers=1, d_ffn=512))[0] == sfb.SF_EINVAL    # widths must agree
+    assert create(cfg(n_q_heads=6), cfg(n_layers=1, n_q_heads=6))[0] == sfb.SF_EINVAL   # Hq % Hkv
+    assert create(cfg(), cfg(n_layers=1), B=0)[0] == sfb.SF_EINVAL
+    assert create(cfg(), cfg(n_layers=1), k=16)[0] == sfb.SF_EINVAL
+    bf = dict(dtype=sfb.SF_BF16, head_dim=96, d_model=384)
+    assert create(cfg(**bf), cfg(n_layers=1, **bf))[0] == sfb.SF_EUNSUPPORTED   # bf16 head_dim
+    wide = dict(dtype=sfb.SF_BF16, n_q_heads=32, n_kv_heads=2, head_dim=64, d_model=2048)
+    assert create(cfg(**wide), cfg(n_layers=1, **wide), k=4)[0] == sfb.SF_EUNSUPPORTED  # 16*5 rows > 64
+
+
+def test_steps_reject_bad_state_before_launching_anything():
+    L = sfb.lib()
+    st, ctx = create(cfg(), cfg(n_layers=1))
+    assert st == sfb.SF_OK
+    s = sfb.State()
+    s.B, s.cap = 4, 128
+    # not bound yet
+    assert L.sf_verify_step(ctx, C.byref(s), 4, None, 0, None, None) == sfb.SF_ESTATE
+    # bind with a missing pointer
+    tw = sfb.TargetWeights()
+    assert L.sf_bind(ctx, C.byref(tw), None) == sfb.SF_EINVAL
+    fake = 0x1000
+    arr = (C.c_void_p * 2)(fake, fake)
+    for n, _ in sfb.TargetWeights._fields_:
+        setattr(tw, n, arr if n not in ("embed", "lm_head", "final_norm") else fake)
+    assert L.sf_bind(ctx, C.byref(tw), None) == sfb.SF_OK
+    # draft step needs draft weights
+    assert L.sf_draft_step(ctx, C.byref(s), 4, 1, 0, None, None) == sfb.SF_ESTATE
+    # null state buffers
+    assert L.sf_verify_step(ctx, C.byref(s), 4, None, 0, None, None) == sfb.SF_EINVAL
+    for n in ("tk", "tv", "dk", "dv", "kv_len", "pending", "hooks", "n_new", "cu_new"):
+        setattr(s, n, fake)
+    s.workspace, s.workspace_bytes = 0x10000, 16
+    assert L.sf_verify_step(ctx, C.byref(s), 4, fake, 0, fake, None) == sfb.SF_ECAPACITY   # workspace
+    s.workspace_bytes = L.sf_workspace_bytes(ctx, 4, 4, 128)
+    assert L.sf_verify_step(ctx, C.byref(s), 5, fake, 0, fake, None) == sfb.SF_EINVAL      # k > max_k
+    assert L.sf_verify_step(ctx, C.byref(s), 4, fake, 124, fake, None) == sfb.SF_ECAPACITY  # 124+5 > 128
+    assert L.sf_verify_step(ctx, C.byref(s), 4, None, 0, fake, None) == sfb.SF_EINVAL      # no draft tokens
+    s.workspace = 0x10010
+    assert L.sf_verify_step(ctx, C.byref(s), 4, fake, 0, fake, None) == sfb.SF_EINVAL      # misaligned
+    assert L.sf_accept_commit(ctx, C.byref(s), 4, fake, None, None, fake, fake, None) == sfb.SF_EINVAL
+    assert L.sf_last_hip_error(ctx) == 0
+    assert b"capacity" in L.sf_strerror(sfb.SF_ECAPACITY)
+    L.sf_destroy(ctx)
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(sfb, "_lib", None)
+    monkeypatch.setattr(sfb, "LIB_PATH", "/nonexistent/libspecformer.so")
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        sfb.lib()

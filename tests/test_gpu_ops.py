@@ -1,0 +1,181 @@
+"""GPU parity of the single operations of the path against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import sfo
+from paper_2511_20340_amd import binding as sfb
+
+from gpu_common import dev, engine_only, rel_err, to_np
+
+pytestmark = pytest.mark.gpu
+
+BF16_TOL = 2e-2     # max relative error w.r.t. max |ref|, bf16 mode
+F32_TOL = 1e-4      # fp32 mode
+
+
+def shape_for(dtype, Hq, Hkv, hd, d=None):
+    d = d or Hq * hd
+    return synth.ModelShape("t", 1, d, Hq, Hkv, hd, 256, 512, dtype)
+
+
+def run_attention(dtype, B, nq, Hq, Hkv, hd, cap, lens, mode, seed=1, poison=False):
+    q, kc, vc = synth.random_qkv(seed, B, nq, Hq, Hkv, hd, cap, dtype)
+    lens = np.asarray(lens, np.int32)
+    ref = sfo.attention(q, kc, vc, lens, mode)
+    kc_g, vc_g = kc.copy(), vc.copy()
+    if poison:                               # dead slots beyond len+nq hold NaN / huge values
+        for b in range(B):
+            kc_g[b, :, lens[b] + nq:] = np.nan
+            vc_g[b, :, lens[b] + nq:] = np.nan
+    eng = engine_only(shape_for(dtype, Hq, Hkv, hd), B, cap, nq - 1 if nq > 1 else 1)
+    eng.sf_kv_import(kc_g, "dk"); eng.sf_kv_import(vc_g, "dv")
+    kvl = torch.from_numpy(lens).cuda()
+    out = eng.sf_op_attention(dev(q, dtype), eng.dk, eng.dv, kvl, nq, mode)
+    torch.cuda.synchronize()
+    return to_np(out), ref
+
+
+@pytest.mark.parametrize("mode", [sfb.SF_MASK_CAUSAL, sfb.SF_MASK_BIDIR])
+@pytest.mark.parametrize("Hq,Hkv,hd,nq", [(8, 2, 128, 5), (10, 2, 128, 5), (8, 2, 64, 5), (8, 2, 128, 7),
+                                          (4, 4, 128, 1), (16, 2, 128, 5)])
+def test_attention_bf16_ragged(mode, Hq, Hkv, hd, nq):
+    # lengths span: empty prefix, inside one tile, tile boundary, several chunks + ragged tail
+    lens = [0, 27, 32, 1500, 511, 2000]
+    got, ref = run_attention("bf16", 6, nq, Hq, Hkv, hd, 2048, lens, mode)
+    assert np.all(np.isfinite(got))
+    assert rel_err(got, ref) < BF16_TOL
+
+
+def test_attention_bf16_ignores_dead_slots():
+    lens = [0, 27, 700, 1000]
+    got, ref = run_attention("bf16", 4, 5, 8, 2, 128, 1024, lens, sfb.SF_MASK_CAUSAL, poison=True)
+    assert np.all(np.isfinite(got))
+    assert rel_err(got, ref) < BF16_TOL
+
+
+def test_attention_bf16_single_slot_equals_both_masks():
+    lens = [5, 900]
+    a, ref = run_attention("bf16", 2, 1, 8, 2, 128, 1024, lens, sfb.SF_MASK_CAUSAL)
+    b, _ = run_attention("bf16", 2, 1, 8, 2, 128, 1024, lens, sfb.SF_MASK_BIDIR)
+    np.testing.assert_array_equal(a, b)          # k = 1: hybrid mask == causal decode
+
+
+@pytest.mark.parametrize("mode", [sfb.SF_MASK_CAUSAL, sfb.SF_MASK_BIDIR])
+def test_attention_f32(mode):
+    lens = [0, 64, 700, 33]
+    got, ref = run_attention("f32", 4, 5, 4, 4, 64, 768, lens, mode)
+    assert rel_err(got, ref) < F32_TOL
+    got, ref = run_attention("f32", 4, 3, 8, 2, 32, 768, lens, mode, seed=2)
+    assert rel_err(got, ref) < F32_TOL
+
+
+@pytest.mark.parametrize("M,N,K", [(320, 512, 4096), (77, 264, 200), (160, 3072, 2048), (640, 384, 1024),
+                                   (1, 128, 64), (333, 1000, 520)])
+def test_linear_bf16(M, N, K):
+    g = synth.rng(5, M * 7 + N)
+    x = synth.to_bf16_values(g.standard_normal((M, K), dtype=np.float32))
+    w = synth.to_bf16_values(g.standard_normal((N, K), dtype=np.float32) * 0.05)
+    bias = synth.to_bf16_values(g.standard_normal(N, dtype=np.float32))
+    res = synth.to_bf16_values(g.standard_normal((M, N), dtype=np.float32))
+    eng = engine_only(shape_for("bf16", 2, 2, 64), 1, 64, 1)
+    ref = sfo.linear(x, w)
+    y = eng.sf_op_linear(dev(x, "bf16"), dev(w, "bf16"), out_f32=True)
+    assert rel_err(to_np(y), ref) < 1e-5          # fp32 accumulators, unrounded
+    y = eng.sf_op_linear(dev(x, "bf16"), dev(w, "bf16"))
+    assert rel_err(to_np(y), ref) < BF16_TOL
+    ref2 = sfo.linear(x, w, bias) + res
+    y = eng.sf_op_linear(dev(x, "bf16"), dev(w, "bf16"), bias=dev(bias, "bf16"), residual=dev(res, "bf16"))
+    assert rel_err(to_np(y), ref2) < BF16_TOL
+    r, xd, wd = dev(res, "bf16"), dev(x, "bf16"), dev(w, "bf16")     # residual aliasing the output
+    sfb.check(eng.lib.sf_op_linear(eng.ctx, xd.data_ptr(), wd.data_ptr(), None,
+                                   r.data_ptr(), r.data_ptr(), M, N, K, 0, None), "alias")
+    torch.cuda.synchronize()
+    assert rel_err(to_np(r), sfo.linear(x, w) + res) < BF16_TOL
+
+
+@pytest.mark.parametrize("M,N,K", [(20, 768, 256), (77, 264, 200), (130, 1024, 1024)])
+def test_linear_f32(M, N, K):
+    g = synth.rng(6, M + N)
+    x = g.standard_normal((M, K), dtype=np.float32)
+    w = g.standard_normal((N, K), dtype=np.float32) * 0.05
+    bias = g.standard_normal(N, dtype=np.float32)
+    eng = engine_only(shape_for("f32", 2, 2, 64), 1, 64, 1)
+    y = eng.sf_op_linear(dev(x, "f32"), dev(w, "f32"), bias=dev(bias, "f32"))
+    assert rel_err(to_np(y), sfo.linear(x, w, bias)) < 1e-5
+
+
+@pytest.mark.parametrize("dtype,tol", [("bf16", BF16_TOL), ("f32", 1e-5)])
+def test_rmsnorm_and_group_rmsnorm(dtype, tol):
+    g = synth.rng(7, 1)
+    d = 520
+    x = g.standard_normal((24, d), dtype=np.float32) * 3
+    gain = 1 + 0.1 * g.standard_normal((4, d), dtype=np.float32)
+    if dtype == "bf16":
+        x, gain = synth.to_bf16_values(x), synth.to_bf16_values(gain)
+    eng = engine_only(shape_for(dtype, 2, 2, 64), 1, 64, 1)
+    y = eng.sf_op_rmsnorm(dev(x, dtype), dev(gain[0], dtype))
+    assert rel_err(to_np(y), sfo.rmsnorm(x, gain[0])) < tol
+    y = eng.sf_op_rmsnorm(dev(x, dtype), dev(gain, dtype), n_gain=4)      # rows [6][4][d]
+    assert rel_err(to_np(y), sfo.group_rmsnorm(x.reshape(6, 4, d), gain).reshape(24, d)) < tol
+
+
+@pytest.mark.parametrize("dtype,tol,hd", [("bf16", BF16_TOL, 128), ("bf16", BF16_TOL, 64), ("f32", 1e-5, 64)])
+def test_rope_kv_append_and_layout_roundtrip(dtype, tol, hd):
+    B, nq, Hq, Hkv, cap = 3, 5, 4, 2, 4096 + 64
+    lens = np.array([0, 1000, 4096], np.int32)           # large positions: table must stay accurate
+    g = synth.rng(8, hd)
+    qkv = g.standard_normal((B * nq, (Hq + 2 * Hkv) * hd), dtype=np.float32)
+    if dtype == "bf16":
+        qkv = synth.to_bf16_values(qkv)
+    eng = engine_only(shape_for(dtype, Hq, Hkv, hd), B, cap, nq - 1)
+    # layout round trip first: import random plain caches, export them back bit-exactly
+    _, kc, vc = synth.random_qkv(3, B, 1, Hq, Hkv, hd, cap, dtype)
+    eng.sf_kv_import(kc, "dk"); eng.sf_kv_import(vc, "dv")
+    np.testing.assert_array_equal(to_np(eng.sf_kv_export("dk")), kc)
+    np.testing.assert_array_equal(to_np(eng.sf_kv_export("dv")), vc)
+    q_out = eng.sf_op_rope_kv_append(dev(qkv, dtype), torch.from_numpy(lens).cuda(), nq, eng.dk, eng.dv)
+    pos = (lens[:, None] + np.arange(nq)[None]).reshape(-1).astype(np.int32)
+    nqc, nkv = Hq * hd, Hkv * hd
+    q_ref = sfo.rope(qkv[:, :nqc].reshape(-1, Hq, hd), pos).reshape(-1, nqc)
+    k_ref = sfo.rope(qkv[:, nqc:nqc + nkv].reshape(-1, Hkv, hd), pos)
+    v_ref = qkv[:, nqc + nkv:].reshape(-1, Hkv, hd)
+    assert rel_err(to_np(q_out), q_ref) < tol
+    kg, vg = to_np(eng.sf_kv_export("dk")), to_np(eng.sf_kv_export("dv"))
+    want_k, want_v = kc.astype(np.float64).copy(), vc.astype(np.float64).copy()
+    for b in range(B):
+        for i in range(nq):
+            want_k[b, :, lens[b] + i] = k_ref[b * nq + i]
+            want_v[b, :, lens[b] + i] = v_ref[b * nq + i]
+    assert rel_err(kg, want_k) < tol
+    np.testing.assert_array_equal(vg, want_v)             # V is copied, not transformed
+    untouched = np.ones((B, cap), bool)
+    for b in range(B):
+        untouched[b, lens[b]:lens[b] + nq] = False
+    np.testing.assert_array_equal(kg.transpose(0, 2, 1, 3)[untouched], kc.transpose(0, 2, 1, 3)[untouched])
+
+
+@pytest.mark.parametrize("dtype,tol", [("bf16", BF16_TOL), ("f32", 1e-5)])
+def test_silu_mul(dtype, tol):
+    g = synth.rng(9, 1)
+    gu = g.standard_normal((37, 2 * 520), dtype=np.float32) * 3
+    eng = engine_only(shape_for(dtype, 2, 2, 64), 1, 64, 1)
+    act = eng.sf_op_silu_mul(torch.from_numpy(gu).cuda())
+    assert rel_err(to_np(act), sfo.silu_mul(gu[:, :520], gu[:, 520:])) < tol
+
+
+@pytest.mark.parametrize("V", [1000, 1024, 32000, 128256, 7])
+def test_argmax_bit_exact(V):
+    g = synth.rng(10, V)
+    M = 23
+    lg = g.standard_normal((M, V), dtype=np.float32)
+    lg[0, :] = 0.5                                 # all tied -> index 0
+    lg[1, [V - 1, V // 2]] = 9.0                   # tie -> lowest index
+    lg[2, 0] = np.nan; lg[2, V - 1] = 50.0         # NaN never wins
+    lg[3, :] = -np.inf
+    lg[4, :] = np.nan
+    eng = engine_only(shape_for("bf16", 2, 2, 64), 1, 64, 1)
+    ids = eng.sf_op_argmax(torch.from_numpy(lg).cuda()).cpu().numpy()
+    want = np.array([sfo.argmax(lg[r]) for r in range(M)], np.int32)
+    np.testing.assert_array_equal(ids, want)
