@@ -1,0 +1,311 @@
+#!/usr/bin/env python3
+"""Benchmark of the SpecFormer draft -> verify -> accept step on one MI355X.
+
+A "step" is one pass of the whole hot path (sf_draft_step, sf_verify_step, sf_accept_commit) over
+the batch.  Inputs (weights, prompts, caches after a real chunked prefill) are resident in HBM
+before the timed region.  Prints ONE JSON line: accepted tokens/s, the roofline of the dominant
+kernel class (per-kernel HIP-event timings collected in a second, identical pass), and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK = 8.0e12
+MFMA_BF16_PEAK = 2.5e15
+FP32_PEAK = 157.3e12
+# kappa (mean tokens per target call) of the paper's model-size table at k=4 / k=2, by model class
+PAPER_KAPPA = {"1b-bf16": 1.84, "8b-bf16": 1.75, "14b-bf16": 1.71, "tiny-f32": 1.84}
+
+
+def solve_alpha(kappa, k):
+    """Per-slot acceptance probability alpha with 1 + a + a^2 + ... + a^k == kappa."""
+    lo, hi = 0.0, 1.0
+    for _ in range(60):
+        mid = 0.5 * (lo + hi)
+        if sum(mid ** i for i in range(k + 1)) < kappa:
+            lo = mid
+        else:
+            hi = mid
+    return 0.5 * (lo + hi)
+
+
+def device_weights(m, k, seed, torch):
+    """Random-init weights generated directly on the GPU (N(0, 0.02^2), norm gains 1)."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    dt = torch.bfloat16 if m.dtype == "bf16" else torch.float32
+
+    def rnd(*shape):
+        return (torch.randn(*shape, generator=g, device="cuda", dtype=torch.float32) * 0.02).to(dt)
+
+    def ones(*shape):
+        return torch.ones(*shape, device="cuda", dtype=dt)
+    d, hd, F, V, L = m.d_model, m.head_dim, m.d_ffn, m.vocab, m.n_layers
+    nqkv = (m.n_q_heads + 2 * m.n_kv_heads) * hd
+    tw = {"embed": rnd(V, d), "lm_head": rnd(V, d), "final_norm": ones(d),
+          "attn_norm": [ones(d) for _ in range(L)], "wqkv": [rnd(nqkv, d) for _ in range(L)],
+          "wo": [rnd(d, m.n_q_heads * hd) for _ in range(L)], "ffn_norm": [ones(d) for _ in range(L)],
+          "w_gate_up": [rnd(2 * F, d) for _ in range(L)], "w_down": [rnd(d, F) for _ in range(L)]}
+    dw = {"group_norm": ones(4, d), "w_ds": rnd(d, 4 * d), "pos_norm": ones(d), "w_pos": rnd(max(k, 1) * d, d),
+          "b_pos": rnd(max(k, 1) * d), "attn_norm": ones(d), "wqkv": rnd(nqkv, d), "wo": rnd(d, m.n_q_heads * hd),
+          "ffn_norm": ones(d), "w_gate_up": rnd(2 * F, d), "w_down": rnd(d, F), "out_norm": ones(d)}
+    return tw, dw
+
+
+def gemm_shapes(m, B, k, qm):
+    """(M, N, K, out_bytes_per_elem, has_residual) of every linear launch in one step."""
+    es = 2 if m.dtype == "bf16" else 4
+    d, F, V = m.d_model, m.d_ffn, m.vocab
+    nq, nkv = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim
+    M, Mh, Ms = B * (k + 1), B * qm, B * k
+    layer = lambda rows: [(rows, nq + 2 * nkv, d, es, 0), (rows, d, nq, es, 1), (rows, 2 * F, d, 4, 0),
+                          (rows, d, F, es, 1)]
+    out = layer(M) * m.n_layers + [(M, V, d, 4, 0)]
+    if k > 0:
+        out += [(Mh, d, 4 * d, es, 0), (Mh, 2 * nkv, d, es, 0), (B, k * d, d, es, 0)] + layer(Ms) + [(Ms, V, d, 4, 0)]
+    return out
+
+
+def gemm_work(shapes, es):
+    by = sum(K * N * es + M * K * es + M * N * ob + (M * N * es if res else 0) for M, N, K, ob, res in shapes)
+    fl = sum(2.0 * M * N * K for M, N, K, _, _ in shapes)
+    return by, fl
+
+
+def cpu_baseline(wl, seed, budget_s=25.0):
+    """The oracle, as it stands, on a bounded sample: B' = 2 sequences of the same model at the
+    workload's prefix length, seeded caches, natural drafts; whole steps (draft + verify + accept)."""
+    import synth
+    from oracle import sfo
+    m, k = wl.model, wl.k
+    Bp = min(2, wl.batch)
+    prefix = int((wl.prefix_lo + wl.prefix_hi) // 2)
+    cap = synth.kv_capacity(prefix, 4, k)
+    t0 = time.time()
+    tw = synth.target_weights(m, seed)
+    dw = synth.draft_weights(m, k, seed)
+    orc = sfo.Oracle(m.cfg(), tw, dw, Bp, cap, q_max=k + 1)
+    g = synth.rng(seed, 777)
+    for name in ("tk", "tv", "dk", "dv"):
+        getattr(orc, name)[...] = g.standard_normal(getattr(orc, name).shape, dtype=np.float32)
+    orc.hooks[...] = g.standard_normal(orc.hooks.shape, dtype=np.float32)
+    orc.kv_len[:] = prefix
+    orc.n_new[:] = 1
+    orc.pending[:] = g.integers(0, m.vocab, Bp)
+    setup = time.time() - t0
+    steps, tokens, t_used = 0, 0, 0.0
+    while steps < 1 or (t_used < budget_s and steps < 4 and t_used / steps * (steps + 1) < budget_s):
+        t1 = time.time()
+        d = orc.draft_step(k)
+        lg = orc.verify_step(k, d)
+        acc, _ = orc.accept_commit(k, d, lg)
+        t_used += time.time() - t1
+        tokens += int(acc.sum())
+        steps += 1
+    return {"value": tokens / t_used, "unit": "accepted tokens/s", "cores": sfo.ncores(), "kind": "oracle",
+            "sample": f"{steps} whole step(s) (draft+verify+accept) at B'={Bp} of {wl.batch}, all {m.n_layers} layers, "
+                      f"prefix {prefix}, k={k}, seeded caches, natural drafts; fp64 naive C + OpenMP; "
+                      f"{t_used:.1f}s timed, {setup:.1f}s setup; per-sequence cost is batch-independent",
+            "ms_per_step_sample": 1e3 * t_used / steps}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=1, help="index into the baseline's configs (default 1: 1B bf16)")
+    ap.add_argument("--k", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth
+    from paper_2511_20340_amd.engine import Engine
+    from paper_2511_20340_amd import binding as sfb
+
+    wl = synth.WORKLOADS[args.config]
+    m, B = wl.model, wl.batch
+    k = args.k if args.k is not None else wl.k
+    steps = args.steps if args.steps is not None else min(wl.steps, 64)
+    warm = args.warmup
+    es = 2 if m.dtype == "bf16" else 4
+    torch.cuda.set_device(0)
+
+    lens = synth.prefix_lengths(B, wl.prefix_lo, wl.prefix_hi, wl.seed)
+    prompts = synth.prompts(lens, m.vocab, wl.seed)
+    n_pass = 2 if args.no_profile else 3
+    total_steps = n_pass * (steps + warm) + 2
+    cap = synth.kv_capacity(int(lens.max()), total_steps, k)
+    eng = Engine(m.cfg(), B, cap, k)
+    tw, dw = device_weights(m, k, wl.seed, torch)
+    eng.bind(tw, dw)
+    del tw, dw
+
+    t0 = time.time()
+    eng.prefill(prompts)
+    torch.cuda.synchronize()
+    t_prefill = time.time() - t0
+    snap = {n: getattr(eng, n).clone() for n in ("kv_len", "pending", "n_new", "cu_new", "hooks")}
+    len0 = int(lens.max())
+
+    # plain greedy continuation of the target (k = 0 steps), for the calibrated drafts
+    n_ar = total_steps * (k + 1) + k + 2
+    ar = torch.zeros(B, n_ar, dtype=torch.int32, device="cuda")
+    ar[:, 0] = eng.pending
+    none = torch.zeros(B, 0, dtype=torch.int32, device="cuda")
+    lg1 = torch.empty(B, 1, m.vocab, dtype=torch.float32, device="cuda")
+    for j in range(1, n_ar):
+        if eng.len_upper + 1 > cap:
+            break
+        eng.sf_verify_step(0, none, logits_out=lg1)
+        _, out = eng.sf_accept_commit(0, none, lg1)
+        ar[:, j] = out[:, 0]
+    torch.cuda.synchronize()
+    for n, t in snap.items():
+        getattr(eng, n).copy_(t)
+    eng.len_upper = len0
+
+    kappa_t = PAPER_KAPPA.get(m.name, 1.75)
+    alpha = solve_alpha(min(kappa_t, k + 1.0), k) if k > 0 else 0.0
+    gen = torch.Generator(device="cuda"); gen.manual_seed(wl.seed)
+    corrupt = (torch.rand(B, n_ar, generator=gen, device="cuda") > alpha).to(torch.int32)
+    inj = (ar + corrupt) % m.vocab
+    len_t = torch.from_numpy(lens).cuda().to(torch.int64)
+    slot = torch.arange(max(k, 1), device="cuda", dtype=torch.int64)[None, :k]
+
+    draft = torch.zeros(B, k, dtype=torch.int32, device="cuda")
+    logits = torch.empty(B, k + 1, m.vocab, dtype=torch.float32, device="cuda")
+    toks = torch.empty(B, k + 1, dtype=torch.int32, device="cuda")
+
+    def run(n, calibrated, acc_hist=None, len_hist=None, phase_ev=None):
+        for i in range(n):
+            if phase_ev is not None:
+                phase_ev[i][0].record()
+            eng.sf_draft_step(k, draft_out=draft)
+            if calibrated and k > 0:
+                idx = (eng.kv_len.to(torch.int64) - len_t + 1)[:, None] + slot
+                draft.copy_(torch.gather(inj, 1, idx.clamp_(max=n_ar - 1)))
+            if phase_ev is not None:
+                phase_ev[i][1].record()
+            if len_hist is not None:
+                len_hist[i].copy_(eng.kv_len)
+            eng.sf_verify_step(k, draft, logits_out=logits)
+            if phase_ev is not None:
+                phase_ev[i][2].record()
+            eng.sf_accept_commit(k, draft, logits, accept_out=None if acc_hist is None else acc_hist[i],
+                                 tokens_out=toks)
+            if phase_ev is not None:
+                phase_ev[i][3].record()
+
+    def timed_pass(calibrated):
+        run(warm, calibrated)
+        acc = torch.zeros(steps, B, dtype=torch.int32, device="cuda")
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        run(steps, calibrated, acc_hist=acc)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t
+        return dt, int(acc.sum().item())
+
+    dt_nat, tok_nat = timed_pass(False)
+    dt_cal, tok_cal = timed_pass(True)
+
+    result = {
+        "metric": "accepted tokens/s at batch B (draft+verify+accept step)",
+        "value": tok_nat / dt_nat, "unit": "accepted tokens/s", "n_gpus": 1, "steps": steps, "warmup": warm,
+        "ms_per_step": 1e3 * dt_nat / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": m.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "baseline_config_index": args.config, "batch": B, "k": k,
+                   "prefix": [int(wl.prefix_lo), int(wl.prefix_hi)], "layers": m.n_layers, "d_model": m.d_model,
+                   "q_heads": m.n_q_heads, "kv_heads": m.n_kv_heads, "head_dim": m.head_dim, "d_ffn": m.d_ffn,
+                   "vocab": m.vocab, "drafts": "natural (the random-init draft block's own tokens)",
+                   "state": "real chunked prefill through sf_verify_step", "prefill_s": round(t_prefill, 3)},
+        "kappa": tok_nat / (steps * B),
+        "step_us": 1e6 * dt_nat / steps,
+        "calibrated": {"what": "draft tokens replaced after sf_draft_step by the target's greedy continuation, "
+                               "each slot corrupted with probability 1-alpha, so kappa matches the paper's model class",
+                       "kappa_target": kappa_t, "alpha": alpha, "kappa": tok_cal / (steps * B),
+                       "value": tok_cal / dt_cal, "unit": "accepted tokens/s", "ms_per_step": 1e3 * dt_cal / steps},
+    }
+
+    if not args.no_profile:
+        # identical pass with every kernel launch bracketed by HIP events on the launch stream
+        run(warm, True)
+        len_hist = torch.zeros(steps, B, dtype=torch.int32, device="cuda")
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        eng.sf_profile_begin()
+        run(steps, True, len_hist=len_hist, phase_ev=ev)
+        prof = eng.sf_profile_end()
+        torch.cuda.synchronize()
+        phases = {"draft_us": np.mean([e[0].elapsed_time(e[1]) for e in ev]) * 1e3,
+                  "verify_us": np.mean([e[1].elapsed_time(e[2]) for e in ev]) * 1e3,
+                  "accept_us": np.mean([e[2].elapsed_time(e[3]) for e in ev]) * 1e3}
+        result["phase_us_profiled_pass"] = {a: round(float(b), 1) for a, b in phases.items()}
+        qm = k + 1
+        shapes = gemm_shapes(m, B, k, qm)
+        g_bytes, g_flops = gemm_work(shapes, es)
+        lsum = len_hist.to(torch.float64).sum(1).cpu().numpy()        # sum_b kv_len per step
+        kvb = 2 * m.head_dim * es * m.n_kv_heads
+        att_v = m.n_layers * (kvb * (lsum + B * (k + 1)) + 2 * B * (k + 1) * m.n_q_heads * m.head_dim * es)
+        att_d = (kvb * (lsum + B * k) + 2 * B * k * m.n_q_heads * m.head_dim * es) if k > 0 else 0 * lsum
+        att_bytes = float(np.mean(att_v + att_d))
+        att_flops = float(np.mean(4.0 * m.n_q_heads * m.head_dim *
+                                  (m.n_layers * (k + 1) * (lsum + B * (k + 1)) + k * (lsum + B * k))))
+        arg_bytes = 4.0 * m.vocab * B * ((k + 1) + k)
+        kernels = {}
+        for name, (ms, cnt) in prof.items():
+            if cnt == 0:
+                continue
+            ent = {"ms_per_step": ms / steps, "launches_per_step": cnt / steps, "avg_us": 1e3 * ms / cnt}
+            t = ms / steps * 1e-3
+            if name == "linear":
+                hb, mf = g_bytes / t, g_flops / t
+                ent.update({"GB/s": hb / 1e9, "TFLOP/s": mf / 1e12, "frac_hbm": hb / HBM_PEAK,
+                            "frac_mfma": mf / (MFMA_BF16_PEAK if es == 2 else FP32_PEAK),
+                            "bytes_per_step": g_bytes, "flops_per_step": g_flops})
+            elif name == "attention":
+                ent.update({"GB/s": att_bytes / t / 1e9, "frac_hbm": att_bytes / t / HBM_PEAK,
+                            "TFLOP/s": att_flops / t / 1e12, "bytes_per_step": att_bytes})
+            elif name == "argmax":
+                ent.update({"GB/s": arg_bytes / t / 1e9, "frac_hbm": arg_bytes / t / HBM_PEAK,
+                            "bytes_per_step": arg_bytes})
+            kernels[name] = ent
+        result["kernels"] = kernels
+        dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
+        e = kernels[dom]
+        peak_f = MFMA_BF16_PEAK if es == 2 else FP32_PEAK
+        if dom == "linear" and e["frac_mfma"] > e["frac_hbm"]:
+            roof = {"bound": "mfma" if es == 2 else "alu", "achieved": e["TFLOP/s"], "peak": peak_f / 1e12,
+                    "unit": "TFLOP/s", "frac": e["frac_mfma"]}
+        else:
+            roof = {"bound": "hbm", "achieved": e.get("GB/s", 0.0), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                    "frac": e.get("frac_hbm", 0.0)}
+        roof.update({"kernel": dom, "avg_launch_us": e["avg_us"], "launches_per_step": e["launches_per_step"],
+                     "algorithmic_per_launch": (e.get("bytes_per_step", 0.0) if roof["unit"] == "GB/s" else
+                                                e.get("flops_per_step", 0.0)) / e["launches_per_step"],
+                     "traffic": None,
+                     "how": "HIP events around every launch of the class on the launch stream, same steps as the timed pass"})
+        result["roofline"] = roof
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, wl.seed)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

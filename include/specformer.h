@@ -132,13 +132,14 @@ sf_status sf_bind(sf_ctx *ctx, const sf_target_weights *target, const sf_draft_w
  *   those positions (the "(L+1)-th layer" cache); the newest row -> RMS -> W_P + b_P -> k slot
  *   states; slots run one attention (+W_O, residual) and SwiGLU layer at positions kv_len[b]+s,
  *   seeing the whole cached context and the k slots under `mask`; output norm -> target LM head
- *   -> argmax.  draft_tokens: dev [B][k] out.  Slot s predicts the token that follows the pending
- *   token by s+1 places.  n_new[b] == 0 leaves that sequence's cache alone (its draft is then
+ *   -> argmax.  draft_tokens: dev [B][k] out.  draft_logits: dev float [B][k][vocab] out, or NULL to
+ *   keep them in the workspace.  Slot s predicts the token that follows the pending token by s+1
+ *   places.  n_new[b] == 0 leaves that sequence's cache alone (its draft is then
  *   computed from a zero context row and is meaningless).  k == 0: no-op.
  * host_len_upper: any host-known upper bound of max_b kv_len[b]; it sizes the launch grids, so
  * no device read-back is needed.  SF_ECAPACITY when host_len_upper + k > cap. */
 sf_status sf_draft_step(sf_ctx *ctx, const sf_state *st, int32_t k, int32_t mask, int32_t host_len_upper,
-                        int32_t *draft_tokens, void *stream);
+                        int32_t *draft_tokens, float *draft_logits, void *stream);
 
 /* Multi-token verification.  Block row i of sequence b is token (i == 0 ? pending[b] :
  * draft_tokens[b][i-1]) at position kv_len[b]+i.  Runs the target decoder over the B*(k+1) rows
@@ -211,6 +212,16 @@ sf_status sf_op_silu_mul(const sf_ctx *ctx, const float *gu, void *act, int32_t 
 size_t sf_argmax_workspace_bytes(int32_t M);
 sf_status sf_op_argmax(const sf_ctx *ctx, const float *logits, int32_t M, int32_t V, int32_t *ids,
                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* Measurement aid.  Between sf_profile_begin and sf_profile_end every kernel launch of this context
+ * is bracketed by a pair of HIP events on its stream.  sf_profile_end waits for the last one and
+ * returns, per kernel class, the summed duration in ms and the number of launches (host arrays of
+ * n_class >= SF_N_KERNEL_CLASSES entries).  Classes: 0 linear (GEMM), 1 attention, 2 attention
+ * split-KV combine, 3 RMSNorm, 4 rotary + K/V append, 5 SwiGLU gate, 6 embedding / hook copies,
+ * 7 arg-max pass over the logits, 8 arg-max finish / accept-commit. */
+#define SF_N_KERNEL_CLASSES 9
+sf_status sf_profile_begin(sf_ctx *ctx);
+sf_status sf_profile_end(sf_ctx *ctx, double *ms, int32_t *launches, int32_t n_class);
 
 const char *sf_strerror(sf_status s);
 /* HIP error code of the last SF_EHIP on this context (0 if none). host. */

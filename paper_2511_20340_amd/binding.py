@@ -8,12 +8,14 @@ LIB_PATH = os.path.join(HERE, "libspecformer.so")
 SF_OK, SF_EINVAL, SF_ECAPACITY, SF_ESTATE, SF_EHIP, SF_EUNSUPPORTED = range(6)
 SF_BF16, SF_F32 = 0, 1
 SF_MASK_CAUSAL, SF_MASK_BIDIR = 0, 1
+KERNEL_CLASSES = ["linear", "attention", "attention_combine", "rmsnorm", "rope_kv_append", "silu_mul",
+                  "embed_hook", "argmax", "accept"]
 
 EXPORTS = [
     "sf_create", "sf_destroy", "sf_workspace_bytes", "sf_kv_cache_bytes", "sf_bind", "sf_draft_step",
     "sf_verify_step", "sf_accept_commit", "sf_kv_import", "sf_kv_export", "sf_attention_workspace_bytes",
     "sf_op_attention", "sf_op_linear", "sf_op_rmsnorm", "sf_op_rope_kv_append", "sf_op_silu_mul",
-    "sf_argmax_workspace_bytes", "sf_op_argmax", "sf_strerror", "sf_last_hip_error", "sf_version",
+    "sf_argmax_workspace_bytes", "sf_op_argmax", "sf_profile_begin", "sf_profile_end", "sf_strerror", "sf_last_hip_error", "sf_version",
 ]
 
 vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
@@ -66,7 +68,7 @@ def lib():
     L.sf_kv_cache_bytes.argtypes = [vp, i32, i32, i32]
     L.sf_kv_cache_bytes.restype = sz
     L.sf_bind.argtypes = [vp, P(TargetWeights), P(DraftWeights)]
-    L.sf_draft_step.argtypes = [vp, P(State), i32, i32, i32, vp, vp]
+    L.sf_draft_step.argtypes = [vp, P(State), i32, i32, i32, vp, vp, vp]
     L.sf_verify_step.argtypes = [vp, P(State), i32, vp, i32, vp, vp]
     L.sf_accept_commit.argtypes = [vp, P(State), i32, vp, vp, vp, vp, vp, vp]
     L.sf_kv_import.argtypes = [vp, vp, vp, i32, i32, i32, vp]
@@ -81,6 +83,8 @@ def lib():
     L.sf_argmax_workspace_bytes.argtypes = [i32]
     L.sf_argmax_workspace_bytes.restype = sz
     L.sf_op_argmax.argtypes = [vp, vp, i32, i32, vp, vp, sz, vp]
+    L.sf_profile_begin.argtypes = [vp]
+    L.sf_profile_end.argtypes = [vp, P(C.c_double), P(i32), i32]
     L.sf_strerror.argtypes = [i32]
     L.sf_strerror.restype = C.c_char_p
     L.sf_last_hip_error.argtypes = [vp]

@@ -8,7 +8,18 @@
 
 using namespace sf;
 
+// Optional per-kernel-class timing (sf_profile_begin / sf_profile_end): every launch is bracketed
+// by a pair of HIP events on the launch stream.
+enum { K_GEMM = 0, K_ATTN, K_ATTN_COMBINE, K_NORM, K_ROPE, K_SILU, K_EMBED_HOOK, K_ARGMAX, K_ACCEPT, K_NCLASS };
+struct Prof {
+  bool on = false;
+  std::vector<hipEvent_t> ev;  // pairs
+  std::vector<int> cls;
+  size_t used = 0;             // pairs in use
+};
+
 struct sf_ctx {
+  mutable Prof prof;
   sf_model_cfg tc, dc;
   int max_B, max_k;
   bool bound, has_draft;
@@ -94,20 +105,37 @@ struct Run {
     if (e != hipSuccess) { c->hip_err = (int)e; st = SF_EHIP; return false; }
     return true;
   }
+  // enqueue one kernel launch of class `cls`, timed when profiling is on
+  template <class F> void launch(int cls, F f) {
+    if (st != SF_OK) return;
+    Prof &p = c->prof;
+    if (!p.on) { ok(f()); return; }
+    if (p.ev.size() < 2 * (p.used + 1)) {
+      hipEvent_t a, b;
+      if (!ok(hipEventCreate(&a)) || !ok(hipEventCreate(&b))) return;
+      p.ev.push_back(a); p.ev.push_back(b);
+    }
+    if (!ok(hipEventRecord(p.ev[2 * p.used], s))) return;
+    if (!ok(f())) return;
+    if (!ok(hipEventRecord(p.ev[2 * p.used + 1], s))) return;
+    if (p.cls.size() <= p.used) p.cls.resize(p.used + 1);
+    p.cls[p.used++] = cls;
+  }
 };
+#define LAUNCH(cls, expr) r.launch(cls, [&] { return (expr); })
 
 void gemm(Run &r, int dtype, const void *x, const void *w, const void *bias, const void *res, void *y, int M, int N,
           int K, int out_f32) {
   if (r.st != SF_OK) return;
   GemmArgs g{x, w, bias, res, y, M, N, K, out_f32};
-  r.ok(dtype == SF_BF16 ? launch_gemm_bf16(g, r.s) : launch_gemm_f32(g, r.s));
+  LAUNCH(K_GEMM, dtype == SF_BF16 ? launch_gemm_bf16(g, r.s) : launch_gemm_f32(g, r.s));
 }
 
 void norm(Run &r, const sf_model_cfg &m, const void *x, const void *gain, void *y, int M, int n_gain = 1,
           int map = 0, int q = 1, int q_max = 1, const int32_t *n_new = nullptr) {
   if (r.st != SF_OK) return;
   NormArgs n{x, gain, y, M, m.d_model, n_gain, m.rms_eps, map, q, q_max, n_new};
-  r.ok(launch_rmsnorm(n, m.dtype, r.s));
+  LAUNCH(K_NORM, launch_rmsnorm(n, m.dtype, r.s));
 }
 
 void attention(Run &r, const sf_model_cfg &m, const void *q, const void *kc, const void *vc, const int32_t *kv_len,
@@ -120,7 +148,8 @@ void attention(Run &r, const sf_model_cfg &m, const void *q, const void *kc, con
   a.chunk_tiles = attn_chunk_tiles(len_upper, n_q);
   const int n_tiles = (len_upper + n_q + TK - 1) / TK;
   a.n_chunks = (n_tiles + a.chunk_tiles - 1) / a.chunk_tiles;
-  r.ok(m.dtype == SF_BF16 ? launch_attention_bf16(a, r.s) : launch_attention_f32(a, r.s));
+  LAUNCH(K_ATTN, m.dtype == SF_BF16 ? launch_attention_bf16(a, r.s) : launch_attention_f32(a, r.s));
+  if (m.dtype == SF_BF16 && a.n_chunks > 1) LAUNCH(K_ATTN_COMBINE, launch_attention_combine(a, r.s));
 }
 
 size_t kv_layer_bytes(const sf_model_cfg &m, int B, int cap) {
@@ -169,6 +198,7 @@ sf_status sf_create(const sf_model_cfg *t, const sf_model_cfg *d, int32_t max_B,
 
 sf_status sf_destroy(sf_ctx *c) {
   if (!c) return SF_EINVAL;
+  for (hipEvent_t e : c->prof.ev) (void)hipEventDestroy(e);
   delete c;
   return SF_OK;
 }
@@ -226,29 +256,29 @@ sf_status sf_verify_step(sf_ctx *c, const sf_state *st, int32_t k, const int32_t
   const int d = m.d_model, F = m.d_ffn, L = m.n_layers;
   const int nq = m.n_q_heads * m.head_dim, nkv = m.n_kv_heads * m.head_dim;
   Run r{c, (hipStream_t)stream};
-  r.ok(launch_embed(c->tw.embed, st->pending, draft, h, st->hooks, B, k, qm, d, m.vocab, m.dtype, r.s));
+  LAUNCH(K_EMBED_HOOK, launch_embed(c->tw.embed, st->pending, draft, h, st->hooks, B, k, qm, d, m.vocab, m.dtype, r.s));
   RopeArgs ra{};
   ra.qkv = qkv; ra.q_out = qr; ra.kv_len = st->kv_len; ra.n_new = nullptr; ra.table = (float2 *)(ws + A.table);
   ra.B = B; ra.n_q = q; ra.Hq = m.n_q_heads; ra.Hkv = m.n_kv_heads; ra.hd = m.head_dim; ra.cap = cap;
   ra.kv_only = 0; ra.pos_mode = 0; ra.theta = m.rope_theta;
-  if (r.st == SF_OK) r.ok(launch_rope_table(ra, r.s));
+  LAUNCH(K_ROPE, launch_rope_table(ra, r.s));
   const int hook_layer[4] = {0, L / 2, L - 1, L};
   const size_t lb = kv_layer_bytes(m, B, cap);
   for (int l = 0; l <= L && r.st == SF_OK; ++l) {
     for (int g = 1; g < 4; ++g)
-      if (hook_layer[g] == l && r.st == SF_OK) r.ok(launch_hook_copy(h, st->hooks, B, q, qm, d, g, m.dtype, r.s));
+      if (hook_layer[g] == l) LAUNCH(K_EMBED_HOOK, launch_hook_copy(h, st->hooks, B, q, qm, d, g, m.dtype, r.s));
     if (l == L) break;
     void *kc = (char *)st->tk + l * lb, *vc = (char *)st->tv + l * lb;
     norm(r, m, h, c->attn_norm[l], a, M);
     gemm(r, m.dtype, a, c->wqkv[l], nullptr, nullptr, qkv, M, nq + 2 * nkv, d, 0);
     ra.kc = kc; ra.vc = vc;
-    if (r.st == SF_OK) r.ok(launch_rope_kv(ra, m.dtype, r.s));
+    LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
     attention(r, m, qr, kc, vc, st->kv_len, ao, (float *)(ws + A.part_o), (float *)(ws + A.part_ml), B, q, cap,
               SF_MASK_CAUSAL, len_upper);
     gemm(r, m.dtype, ao, c->wo[l], nullptr, h, h, M, d, nq, 0);
     norm(r, m, h, c->ffn_norm[l], a, M);
     gemm(r, m.dtype, a, c->w_gate_up[l], nullptr, nullptr, gu, M, 2 * F, d, 1);
-    if (r.st == SF_OK) r.ok(launch_silu_mul(gu, act, M, F, m.dtype, r.s));
+    LAUNCH(K_SILU, launch_silu_mul(gu, act, M, F, m.dtype, r.s));
     gemm(r, m.dtype, act, c->w_down[l], nullptr, h, h, M, d, F, 0);
   }
   norm(r, m, h, c->tw.final_norm, a, M);
@@ -257,7 +287,7 @@ sf_status sf_verify_step(sf_ctx *c, const sf_state *st, int32_t k, const int32_t
 }
 
 sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, int32_t len_upper,
-                        int32_t *draft_tokens, void *stream) {
+                        int32_t *draft_tokens, float *draft_logits, void *stream) {
   sf_status v = check_state(c, st, k, true);
   if (v != SF_OK) return v;
   if (k == 0) return SF_OK;
@@ -270,7 +300,7 @@ sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, 
   char *ws = (char *)st->workspace;
   void *a = ws + A.a, *qkv = ws + A.qkv, *qr = ws + A.qr, *ao = ws + A.ao, *act = ws + A.act;
   void *f4 = ws + A.f4, *x = ws + A.x, *kvc = ws + A.kvc, *xl = ws + A.xl, *s0 = ws + A.s0;
-  float *gu = (float *)(ws + A.gu), *dlogits = (float *)(ws + A.dlogits);
+  float *gu = (float *)(ws + A.gu), *dlogits = draft_logits ? draft_logits : (float *)(ws + A.dlogits);
   const int d = m.d_model, F = m.d_ffn;
   const int nq = m.n_q_heads * m.head_dim, nkv = m.n_kv_heads * m.head_dim;
   const size_t es = esize(m.dtype);
@@ -286,8 +316,8 @@ sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, 
   ra.table = (float2 *)(ws + A.table);
   ra.B = B; ra.n_q = qm; ra.Hq = m.n_q_heads; ra.Hkv = m.n_kv_heads; ra.hd = m.head_dim; ra.cap = cap;
   ra.kv_only = 1; ra.pos_mode = 1; ra.theta = m.rope_theta;
-  if (r.st == SF_OK) r.ok(launch_rope_table(ra, r.s));
-  if (r.st == SF_OK) r.ok(launch_rope_kv(ra, m.dtype, r.s));
+  LAUNCH(K_ROPE, launch_rope_table(ra, r.s));
+  LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
   // positional FFN on the newest committed row -> k slot states
   norm(r, m, x, w.pos_norm, xl, B, 1, 2, qm, qm, st->n_new);
   gemm(r, m.dtype, xl, w.w_pos, w.b_pos, nullptr, s0, B, k * d, d, 0);
@@ -295,21 +325,19 @@ sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, 
   norm(r, m, s0, w.attn_norm, a, Ms);
   gemm(r, m.dtype, a, w.wqkv, nullptr, nullptr, qkv, Ms, nq + 2 * nkv, d, 0);
   ra.qkv = qkv; ra.q_out = qr; ra.n_new = nullptr; ra.n_q = k; ra.kv_only = 0; ra.pos_mode = 0;
-  if (r.st == SF_OK) r.ok(launch_rope_table(ra, r.s));
-  if (r.st == SF_OK) r.ok(launch_rope_kv(ra, m.dtype, r.s));
+  LAUNCH(K_ROPE, launch_rope_table(ra, r.s));
+  LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
   attention(r, m, qr, st->dk, st->dv, st->kv_len, ao, (float *)(ws + A.part_o), (float *)(ws + A.part_ml), B, k,
             cap, mask, len_upper);
   gemm(r, m.dtype, ao, w.wo, nullptr, s0, s0, Ms, d, nq, 0);
   norm(r, m, s0, w.ffn_norm, a, Ms);
   gemm(r, m.dtype, a, w.w_gate_up, nullptr, nullptr, gu, Ms, 2 * F, d, 1);
-  if (r.st == SF_OK) r.ok(launch_silu_mul(gu, act, Ms, F, m.dtype, r.s));
+  LAUNCH(K_SILU, launch_silu_mul(gu, act, Ms, F, m.dtype, r.s));
   gemm(r, m.dtype, act, w.w_down, nullptr, s0, s0, Ms, d, F, 0);
   norm(r, m, s0, w.out_norm, a, Ms);
   gemm(r, m.dtype, a, c->tw.lm_head, nullptr, nullptr, dlogits, Ms, m.vocab, d, 1);
-  if (r.st == SF_OK)
-    r.ok(launch_argmax_partial(dlogits, Ms, m.vocab, (float *)(ws + A.pmax), (int32_t *)(ws + A.pidx), r.s));
-  if (r.st == SF_OK)
-    r.ok(launch_argmax_final((float *)(ws + A.pmax), (int32_t *)(ws + A.pidx), Ms, draft_tokens, r.s));
+  LAUNCH(K_ARGMAX, launch_argmax_partial(dlogits, Ms, m.vocab, (float *)(ws + A.pmax), (int32_t *)(ws + A.pidx), r.s));
+  LAUNCH(K_ACCEPT, launch_argmax_final((float *)(ws + A.pmax), (int32_t *)(ws + A.pidx), Ms, draft_tokens, r.s));
   return r.st;
 }
 
@@ -322,10 +350,10 @@ sf_status sf_accept_commit(sf_ctx *c, const sf_state *st, int32_t k, const int32
   char *ws = (char *)st->workspace;
   Run r{c, (hipStream_t)stream};
   const int M = st->B * (k + 1);
-  r.ok(launch_argmax_partial(logits, M, c->tc.vocab, (float *)(ws + A.pmax), (int32_t *)(ws + A.pidx), r.s));
+  LAUNCH(K_ARGMAX, launch_argmax_partial(logits, M, c->tc.vocab, (float *)(ws + A.pmax), (int32_t *)(ws + A.pidx), r.s));
   AcceptArgs a{(float *)(ws + A.pmax), (int32_t *)(ws + A.pidx), draft, force_len, accept_len, out_tokens,
                st->kv_len, st->pending, st->n_new, st->cu_new, st->B, k};
-  if (r.st == SF_OK) r.ok(launch_accept(a, r.s));
+  LAUNCH(K_ACCEPT, launch_accept(a, r.s));
   return r.st;
 }
 
@@ -387,7 +415,7 @@ sf_status sf_op_rmsnorm(const sf_ctx *c, const void *x, const void *gain, void *
   if (!c || !x || !gain || !y || M < 1 || d < 1 || n_gain < 1) return SF_EINVAL;
   NormArgs n{x, gain, y, M, d, n_gain, c->tc.rms_eps, 0, 1, 1, nullptr};
   Run r{c, (hipStream_t)stream};
-  r.ok(launch_rmsnorm(n, c->tc.dtype, r.s));
+  LAUNCH(K_NORM, launch_rmsnorm(n, c->tc.dtype, r.s));
   return r.st;
 }
 
@@ -403,15 +431,15 @@ sf_status sf_op_rope_kv_append(const sf_ctx *c, const void *qkv, const int32_t *
   ra.B = B; ra.n_q = n_q; ra.Hq = m.n_q_heads; ra.Hkv = m.n_kv_heads; ra.hd = m.head_dim; ra.cap = cap;
   ra.theta = m.rope_theta;
   Run r{c, (hipStream_t)stream};
-  r.ok(launch_rope_table(ra, r.s));
-  if (r.st == SF_OK) r.ok(launch_rope_kv(ra, m.dtype, r.s));
+  LAUNCH(K_ROPE, launch_rope_table(ra, r.s));
+  LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
   return r.st;
 }
 
 sf_status sf_op_silu_mul(const sf_ctx *c, const float *gu, void *act, int32_t M, int32_t F, void *stream) {
   if (!c || !gu || !act || M < 1 || F < 1) return SF_EINVAL;
   Run r{c, (hipStream_t)stream};
-  r.ok(launch_silu_mul(gu, act, M, F, c->tc.dtype, r.s));
+  LAUNCH(K_SILU, launch_silu_mul(gu, act, M, F, c->tc.dtype, r.s));
   return r.st;
 }
 
@@ -426,9 +454,34 @@ sf_status sf_op_argmax(const sf_ctx *c, const float *logits, int32_t M, int32_t 
   float *pmax = (float *)workspace;
   int32_t *pidx = (int32_t *)((char *)workspace + up((size_t)M * ARGMAX_SEGS * sizeof(float)));
   Run r{c, (hipStream_t)stream};
-  r.ok(launch_argmax_partial(logits, M, V, pmax, pidx, r.s));
-  if (r.st == SF_OK) r.ok(launch_argmax_final(pmax, pidx, M, ids, r.s));
+  LAUNCH(K_ARGMAX, launch_argmax_partial(logits, M, V, pmax, pidx, r.s));
+  LAUNCH(K_ACCEPT, launch_argmax_final(pmax, pidx, M, ids, r.s));
   return r.st;
+}
+
+sf_status sf_profile_begin(sf_ctx *c) {
+  if (!c) return SF_EINVAL;
+  c->prof.on = true;
+  c->prof.used = 0;
+  return SF_OK;
+}
+
+sf_status sf_profile_end(sf_ctx *c, double *ms, int32_t *launches, int32_t n_class) {
+  if (!c || !ms || !launches || n_class < K_NCLASS) return SF_EINVAL;
+  Prof &p = c->prof;
+  p.on = false;
+  for (int i = 0; i < n_class; ++i) { ms[i] = 0.0; launches[i] = 0; }
+  if (p.used == 0) return SF_OK;
+  hipError_t e = hipEventSynchronize(p.ev[2 * p.used - 1]);
+  for (size_t i = 0; i < p.used && e == hipSuccess; ++i) {
+    float t = 0.f;
+    e = hipEventElapsedTime(&t, p.ev[2 * i], p.ev[2 * i + 1]);
+    ms[p.cls[i]] += t;
+    launches[p.cls[i]] += 1;
+  }
+  p.used = 0;
+  if (e != hipSuccess) { c->hip_err = (int)e; return SF_EHIP; }
+  return SF_OK;
 }
 
 const char *sf_strerror(sf_status s) {

@@ -362,8 +362,12 @@ hipError_t launch_attention_bf16(const AttnArgs &a, hipStream_t s) {
                                                   a.Hkv, a.cap, a.mode, a.chunk_tiles, a.n_chunks, n_rt,
                                                   scale_log2e);
   }
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess || a.n_chunks <= 1) return e;
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_combine(const AttnArgs &a, hipStream_t s) {
+  const int G = a.Hq / a.Hkv;
+  const int n_rt = (G * a.n_q + 31) / 32;
   dim3 cgrid(a.Hq, a.n_q, a.B);
   if (a.hd == 128)
     attn_combine_kernel<128><<<cgrid, 32, 0, s>>>(a.part_o, a.part_ml, a.kv_len, (bf16_t *)a.out, a.n_q, a.Hq,

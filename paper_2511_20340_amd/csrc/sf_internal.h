@@ -79,6 +79,8 @@ struct AttnArgs {
 int attn_chunk_tiles(int len_upper, int n_q);
 size_t attn_workspace_bytes(int B, int Hkv, int hd, int G, int n_q, int len_upper);
 hipError_t launch_attention_bf16(const AttnArgs &a, hipStream_t s);
+// merges the split-KV partials (only needed when a.n_chunks > 1)
+hipError_t launch_attention_combine(const AttnArgs &a, hipStream_t s);
 hipError_t launch_attention_f32(const AttnArgs &a, hipStream_t s);
 
 struct GemmArgs {

@@ -113,10 +113,10 @@ class Engine:
         sfb.check(self.lib.sf_bind(self.ctx, C.byref(T), C.byref(D) if D is not None else None), "sf_bind")
 
     # ---- the three steps ---------------------------------------------------------------------
-    def sf_draft_step(self, k, mask=sfb.SF_MASK_BIDIR, draft_out=None):
+    def sf_draft_step(self, k, mask=sfb.SF_MASK_BIDIR, draft_out=None, logits_out=None):
         out = draft_out if draft_out is not None else torch.empty(self.B, max(k, 0), dtype=torch.int32, device=self.dev)
-        sfb.check(self.lib.sf_draft_step(self.ctx, C.byref(self.st), k, mask, self.len_upper, _ptr(out), _stream()),
-                  "sf_draft_step")
+        sfb.check(self.lib.sf_draft_step(self.ctx, C.byref(self.st), k, mask, self.len_upper, _ptr(out),
+                                         _ptr(logits_out), _stream()), "sf_draft_step")
         return out
 
     def sf_verify_step(self, k, draft, logits_out=None):
@@ -135,6 +135,16 @@ class Engine:
                   "sf_accept_commit")
         self.len_upper = min(self.len_upper + k + 1, self.cap)
         return acc, out
+
+    def sf_profile_begin(self):
+        sfb.check(self.lib.sf_profile_begin(self.ctx), "sf_profile_begin")
+
+    def sf_profile_end(self):
+        """-> {class name: (total ms, launches)}; waits for the profiled work."""
+        n = len(sfb.KERNEL_CLASSES)
+        ms, cnt = (C.c_double * n)(), (C.c_int32 * n)()
+        sfb.check(self.lib.sf_profile_end(self.ctx, ms, cnt, n), "sf_profile_end")
+        return {name: (ms[i], cnt[i]) for i, name in enumerate(sfb.KERNEL_CLASSES)}
 
     # ---- state helpers (plumbing) ------------------------------------------------------------
     def set_state(self, kv_len=None, pending=None, n_new=None):

@@ -78,7 +78,7 @@ def test_steps_reject_bad_state_before_launching_anything():
         setattr(tw, n, arr if n not in ("embed", "lm_head", "final_norm") else fake)
     assert L.sf_bind(ctx, C.byref(tw), None) == sfb.SF_OK
     # draft step needs draft weights
-    assert L.sf_draft_step(ctx, C.byref(s), 4, 1, 0, None, None) == sfb.SF_ESTATE
+    assert L.sf_draft_step(ctx, C.byref(s), 4, 1, 0, None, None, None) == sfb.SF_ESTATE
     # null state buffers
     assert L.sf_verify_step(ctx, C.byref(s), 4, None, 0, None, None) == sfb.SF_EINVAL
     for n in ("tk", "tv", "dk", "dv", "kv_len", "pending", "hooks", "n_new", "cu_new"):

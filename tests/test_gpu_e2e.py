@@ -1,0 +1,274 @@
+"""End-to-end GPU parity of draft -> verify -> accept against the CPU oracle, through the C ABI.
+
+fp32 (the Tiny configuration, whole run, free-running): logits within 1e-4, ids exact.
+bf16 (reduced slices at real head shapes, teacher-forced from the oracle's state every step):
+logits within 2e-2 of the unrounded oracle; integer outputs exact against the oracle that rounds
+to bf16 at the same tensor boundaries, at positions whose top-2 logit gap exceeds the guard band.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import sfo
+from paper_2511_20340_amd import binding as sfb
+
+from gpu_common import make_pair, rel_err, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_ar(orc, prompts, n_tokens):
+    """Plain greedy decoding with the oracle: the reference continuation of every prompt."""
+    first = orc.prefill(prompts)
+    outs = [[int(t)] for t in first]
+    none = np.zeros((orc.B, 0), np.int32)
+    for _ in range(n_tokens - 1):
+        lg = orc.verify_step(0, none)
+        _, out = orc.accept_commit(0, none, lg)
+        for b in range(orc.B):
+            outs[b].append(int(out[b, 0]))
+    return np.array(outs, np.int32)
+
+
+def injected(ar, emitted, k, V, rng, p_keep):
+    """Drafts = the true continuation, each slot kept with probability p_keep (else off by one)."""
+    B = ar.shape[0]
+    d = np.stack([ar[b, emitted[b]:emitted[b] + k] for b in range(B)]).astype(np.int32)
+    bad = rng.random((B, k)) > p_keep
+    d[bad] = (d[bad] + 1) % V
+    return d
+
+
+def top2_gap(logits):
+    s = np.sort(logits, axis=-1)
+    return s[..., -1] - s[..., -2]
+
+
+def test_tiny_fp32_whole_run():
+    """Configuration 0: 2-layer fp32 decoder, batch 4, prefix 64, k = 4, 16 steps."""
+    wl = synth.WORKLOADS[0]
+    m, B, k, steps = wl.model, wl.batch, wl.k, wl.steps
+    cap = synth.kv_capacity(wl.prefix_hi, steps, k)
+    lens = synth.prefix_lengths(B, wl.prefix_lo, wl.prefix_hi, wl.seed)
+    prompts = synth.prompts(lens, m.vocab, wl.seed)
+    orc_ar, _, _, _ = make_pair(m, B, cap, k, wl.seed)
+    ar = oracle_ar(orc_ar, prompts, steps * (k + 1) + 2)
+    orc, eng, _, _ = make_pair(m, B, cap, k, wl.seed)
+    first_o = orc.prefill(prompts)
+    first_g = eng.prefill(prompts).cpu().numpy()
+    np.testing.assert_array_equal(first_g, first_o)
+    np.testing.assert_array_equal(eng.kv_len.cpu().numpy(), orc.kv_len)
+    rng = np.random.default_rng(wl.seed)
+    emitted = np.ones(B, np.int64)
+    worst, accs = 0.0, []
+    outs = [[int(t)] for t in first_o]
+    for step in range(steps):
+        d_o, dl_o = orc.draft_step(k, want_logits=True)
+        d_g = eng.sf_draft_step(k).cpu().numpy()
+        safe = top2_gap(dl_o) > 1e-3
+        np.testing.assert_array_equal(d_g[safe], d_o[safe])
+        assert safe.mean() > 0.95
+        draft = injected(ar, emitted, k, m.vocab, rng, 0.6) if step % 2 else d_o
+        lg_o = orc.verify_step(k, draft)
+        dg = torch.from_numpy(draft).cuda()
+        lg_g = eng.sf_verify_step(k, dg)
+        worst = max(worst, rel_err(to_np(lg_g), lg_o))
+        acc_o, out_o = orc.accept_commit(k, draft, lg_o)
+        acc_g, out_g = eng.sf_accept_commit(k, dg, lg_g)
+        np.testing.assert_array_equal(acc_g.cpu().numpy(), acc_o)
+        np.testing.assert_array_equal(out_g.cpu().numpy(), out_o)
+        np.testing.assert_array_equal(eng.kv_len.cpu().numpy(), orc.kv_len)
+        np.testing.assert_array_equal(eng.pending.cpu().numpy(), orc.pending)
+        np.testing.assert_array_equal(eng.cu_new.cpu().numpy(), orc.cu_new)
+        accs.append(acc_o.copy())
+        for b in range(B):
+            outs[b] += [int(t) for t in out_o[b, :acc_o[b]]]
+        emitted += acc_o
+    assert worst < 1e-4, worst
+    assert np.max(accs) > 1                                         # acceptance > 1 was exercised
+    for b in range(B):                                              # lossless: equals plain greedy
+        assert outs[b] == list(ar[b, :len(outs[b])])
+    # committed K/V of both caches agree with the oracle's
+    for which, ref in (("tk", orc.tk[0]), ("tv", orc.tv[0]), ("dk", orc.dk), ("dv", orc.dv)):
+        got = to_np(eng.sf_kv_export(which, 0))
+        for b in range(B):
+            n = int(orc.kv_len[b])
+            assert rel_err(got[b, :, :n], ref[b, :, :n]) < 1e-4, which
+    last = m.n_layers - 1
+    got = to_np(eng.sf_kv_export("tk", last))
+    for b in range(B):
+        n = int(orc.kv_len[b])
+        assert rel_err(got[b, :, :n], orc.tk[last][b, :, :n]) < 1e-4
+
+
+def load_state(eng, orc, k):
+    """Teacher forcing: the engine's state becomes the (bf16-rounded) oracle's state."""
+    for l in range(orc.L):
+        eng.sf_kv_import(orc.tk[l], "tk", l)
+        eng.sf_kv_import(orc.tv[l], "tv", l)
+    eng.sf_kv_import(orc.dk, "dk")
+    eng.sf_kv_import(orc.dv, "dv")
+    eng.set_state(kv_len=orc.kv_len, pending=orc.pending, n_new=orc.n_new)
+    hooks = np.zeros((orc.B, k + 1, 4, orc.d), np.float32)
+    n = min(k + 1, orc.hooks.shape[1])
+    hooks[:, :n] = orc.hooks[:, :n]
+    eng.hooks.copy_(torch.from_numpy(hooks).cuda().to(eng.tdtype))
+
+
+SLICES = {
+    # real head shapes of the 1B-class (hd 64, G 4) and 8B-class (hd 128, G 4) workloads, narrow widths
+    "1b-slice": synth.ModelShape("1b-slice", 2, 512, 8, 2, 64, 1536, 2048, "bf16"),
+    "8b-slice": synth.ModelShape("8b-slice", 2, 1024, 8, 2, 128, 2048, 4096, "bf16"),
+    "14b-slice": synth.ModelShape("14b-slice", 3, 1280, 10, 2, 128, 1792, 4096, "bf16"),
+}
+
+
+@pytest.mark.parametrize("name", list(SLICES))
+def test_bf16_slices_teacher_forced(name):
+    m = SLICES[name]
+    B, k, steps, seed = 4, 4, 5, 77
+    lens = np.array([21, 40, 33, 64], np.int32)
+    cap = 128
+    prompts = synth.prompts(lens, m.vocab, seed)
+    # std 0.05: logits spread enough that the guard band leaves most positions testable
+    orc, eng, _, _ = make_pair(m, B, cap, k, seed, std=0.05, round_bf16=True)
+    ref, _, _, _ = make_pair(m, B, cap, k, seed, std=0.05, round_bf16=False)
+    ar = oracle_ar(make_pair(m, B, cap, k, seed, std=0.05, round_bf16=True)[0], prompts, steps * (k + 1) + 2)
+    orc.prefill(prompts)
+    first_g = eng.prefill(prompts).cpu().numpy()      # the GPU's own chunked prefill, checked once
+    assert (first_g == orc.pending).mean() >= 0.75
+
+    def sync_ref():                                   # exact-arithmetic oracle on the same trajectory
+        ref.restore(orc.snapshot())
+    sync_ref()
+    rng = np.random.default_rng(seed)
+    emitted = np.ones(B, np.int64)
+    tested = total = 0
+    errs = []
+    for step in range(steps):
+        # ---- draft, from the oracle's state -------------------------------------------------
+        if step > 0:
+            load_state(eng, orc, k)                           # state BEFORE the draft cache is extended
+        d_o, dl_o = orc.draft_step(k, want_logits=True)       # also fills the oracle's draft cache
+        _, dl_ref = ref.draft_step(k, want_logits=True)
+        if step == 0:
+            load_state(eng, orc, k)
+            # after prefill the oracle holds all prompt rows as "new"; the engine consumes k+1 rows
+            # per call, so hand it the last block only (its draft cache was just imported)
+            nn = np.minimum(orc.n_new, k + 1)
+            hooks = np.zeros((B, k + 1, 4, orc.d), np.float32)
+            for b in range(B):
+                hooks[b, :nn[b]] = orc.hooks[b, orc.n_new[b] - nn[b]:orc.n_new[b]]
+            eng.hooks.copy_(torch.from_numpy(hooks).cuda().to(eng.tdtype))
+            eng.set_state(n_new=nn)
+        dl_g = torch.empty(B, k, m.vocab, dtype=torch.float32, device="cuda")
+        d_g = eng.sf_draft_step(k, logits_out=dl_g).cpu().numpy()
+        dl_g = to_np(dl_g)
+        assert rel_err(dl_g, dl_ref) < 2e-2                   # tolerance leg: exact-arithmetic oracle
+        derr = np.abs(dl_g - dl_o).max()
+        safe = top2_gap(dl_o) > 2.5 * derr                    # an id can only flip inside 2 * error
+        np.testing.assert_array_equal(d_g[safe], d_o[safe])
+        errs.append((float(derr), float(np.abs(dl_o - dl_ref).max())))
+        tested += int(safe.sum()); total += safe.size
+        got = to_np(eng.sf_kv_export("dk"))                   # the draft layer's own cache follows
+        for b in range(B):
+            n = int(orc.kv_len[b]) + k
+            assert rel_err(got[b, :, :n], orc.dk[b, :, :n]) < 2e-2
+        # ---- verify + accept ----------------------------------------------------------------
+        draft = injected(ar, emitted, k, m.vocab, rng, 0.7)
+        lg_o = orc.verify_step(k, draft)
+        dg = torch.from_numpy(draft).cuda()
+        lg_g = eng.sf_verify_step(k, dg)
+        lg_gn = to_np(lg_g)
+        err = np.abs(lg_gn - lg_o).max()
+        assert rel_err(lg_gn, lg_o) < 2e-2
+        ids_o, ids_g = lg_o.argmax(-1), lg_gn.argmax(-1)
+        safe = top2_gap(lg_o) > 2.5 * err
+        np.testing.assert_array_equal(ids_g[safe], ids_o[safe])
+        errs.append((float(err), float(np.abs(lg_o).max())))
+        tested += int(safe.sum()); total += safe.size
+        # hooks and appended K/V of the block
+        hk = to_np(eng.hooks)
+        assert rel_err(hk, orc.hooks[:, :k + 1]) < 2e-2
+        for l in (0, m.n_layers - 1):
+            got = to_np(eng.sf_kv_export("tk", l))
+            for b in range(B):
+                n = int(orc.kv_len[b]) + k + 1
+                assert rel_err(got[b, :, :n], orc.tk[l][b, :, :n]) < 2e-2
+        # acceptance on the GPU's own logits; exact where every compared row is outside the band
+        acc_o, out_o = orc.accept_commit(k, draft, lg_o)
+        acc_g, out_g = eng.sf_accept_commit(k, dg, lg_g)
+        rows_ok = safe.all(axis=1)
+        np.testing.assert_array_equal(acc_g.cpu().numpy()[rows_ok], acc_o[rows_ok])
+        np.testing.assert_array_equal(out_g.cpu().numpy()[rows_ok], out_o[rows_ok])
+        np.testing.assert_array_equal(eng.kv_len.cpu().numpy()[rows_ok], orc.kv_len[rows_ok])
+        emitted += acc_o
+        sync_ref()
+    print(name, "guard-band coverage", tested, total, "errors", errs)
+    assert tested / total > 0.6, (tested, total, errs)
+
+
+def test_bf16_verify_logits_against_unrounded_oracle():
+    """Tolerance leg of the protocol: bf16 GPU logits vs the oracle with NO rounding emulation."""
+    m = SLICES["8b-slice"]
+    B, k, seed, cap = 3, 4, 5, 96
+    prompts = synth.prompts([30, 17, 44], m.vocab, seed)
+    ref, eng, _, _ = make_pair(m, B, cap, k, seed, std=0.05, round_bf16=False)
+    ref.prefill(prompts)
+    eng.prefill(prompts)
+    draft = np.random.default_rng(0).integers(0, m.vocab, (B, k)).astype(np.int32)
+    eng.set_state(pending=ref.pending)
+    lg_o = ref.verify_step(k, draft)
+    lg_g = to_np(eng.sf_verify_step(k, torch.from_numpy(draft).cuda()))
+    assert rel_err(lg_g, lg_o) < 2e-2
+
+
+def run_engine(eng, prompts, k, steps, draft_fn):
+    first = eng.prefill(prompts).cpu().numpy()
+    outs = [[int(t)] for t in first]
+    accs = []
+    for _ in range(steps):
+        nat = eng.sf_draft_step(k) if k > 0 else None
+        d = draft_fn(nat, outs)
+        lg = eng.sf_verify_step(k, d)
+        acc, out = eng.sf_accept_commit(k, d, lg)
+        acc, out = acc.cpu().numpy(), out.cpu().numpy()
+        accs.append(acc)
+        for b in range(eng.B):
+            outs[b] += [int(t) for t in out[b, :acc[b]]]
+    return outs, np.array(accs)
+
+
+@pytest.mark.parametrize("name", ["tiny", "8b-slice"])
+def test_lossless_on_the_gpu(name):
+    """Speculative greedy output of the GPU path == its own plain greedy output (k = 0), for
+    natural, all-wrong and mostly-right drafts."""
+    m = synth.TINY if name == "tiny" else SLICES[name]
+    B, k, steps, seed, cap = 4, 4, 6, 11, 128
+    prompts = synth.prompts([13, 30, 7, 22], m.vocab, seed)
+    _, eng0, _, _ = make_pair(m, B, cap, 0, seed, std=0.05, with_draft=False)
+    ar, _ = run_engine(eng0, prompts, 0, steps * (k + 1) + 1, lambda nat, outs: None)
+    V = m.vocab
+    rng = np.random.default_rng(seed)
+
+    def mostly_right(nat, outs):
+        d = np.array([[ar[b][len(outs[b]) + i] for i in range(k)] for b in range(B)], np.int32)
+        bad = rng.random((B, k)) > 0.7
+        d[bad] = (d[bad] + 1) % V
+        return torch.from_numpy(d).cuda()
+
+    def all_wrong(nat, outs):
+        d = np.array([[(ar[b][len(outs[b]) + i] + 1) % V for i in range(k)] for b in range(B)], np.int32)
+        return torch.from_numpy(d).cuda()
+
+    for fn in (lambda nat, outs: nat, all_wrong, mostly_right):
+        _, eng, _, _ = make_pair(m, B, cap, k, seed, std=0.05)
+        outs, accs = run_engine(eng, prompts, k, steps, fn)
+        for b in range(B):
+            assert outs[b] == ar[b][:len(outs[b])]
+        assert accs.min() >= 1 and accs.max() <= k + 1
+        if fn is all_wrong:
+            assert np.all(accs == 1)
+        if fn is mostly_right:
+            assert accs.max() > 1
