@@ -18,7 +18,9 @@
  *    on the device.  Calls on one sf_ctx must be issued from one thread at a time.
  *  - Tensors are dense row-major, last index fastest.  "elem" is the model dtype: 2-byte bf16 for
  *    SF_BF16, 4-byte IEEE float for SF_F32.  Logits are always float.
- *  - Linear weights are [out_features][in_features] (y = x . W^T).
+ *  - Linear weights are logically [out_features][in_features] (y = x . W^T) and are passed PACKED:
+ *    sf_pack_weight turns a row-major matrix into the MFMA-operand-ordered form the kernels stream
+ *    (bf16; for SF_F32 packing is a plain copy).  The shapes in the weight structs are logical.
  *  - Errors: argument / state problems are reported synchronously by the return code and nothing
  *    is enqueued; a failed HIP launch gives SF_EHIP and sf_last_hip_error() holds the HIP code.
  *
@@ -64,8 +66,8 @@ typedef struct {
 /* Target weights, all dev, elem dtype.  Per-layer arrays are HOST arrays of n_layers dev pointers
  * (copied by sf_bind). */
 typedef struct {
-  const void *embed;              /* [vocab][d]                                    */
-  const void *lm_head;            /* [vocab][d]                                    */
+  const void *embed;              /* [vocab][d]  row-major (gathered, not multiplied) */
+  const void *lm_head;            /* [vocab][d]  packed                            */
   const void *final_norm;         /* [d]                                           */
   const void *const *attn_norm;   /* L x [d]                                       */
   const void *const *wqkv;        /* L x [(Hq+2Hkv)*hd][d]  rows: Q heads, K heads, V heads */
@@ -107,7 +109,8 @@ typedef struct {
   void *hooks;        /* [B][max_k+1][4][d] elem; written by verify, read by draft     */
   int32_t *n_new;     /* [B]   written by accept, read by draft                        */
   int32_t *cu_new;    /* [B+1] written by accept                                       */
-  void *workspace;    /* >= sf_workspace_bytes(ctx, B, k, cap) bytes, 256-byte aligned */
+  void *workspace;    /* >= sf_workspace_bytes(ctx, B, k, cap) bytes, 256-byte aligned,
+                         zero-filled once by the caller after allocation            */
   size_t workspace_bytes;
 } sf_state;
 
@@ -184,12 +187,26 @@ sf_status sf_op_attention(const sf_ctx *ctx, const void *q, const void *kc, cons
                           int32_t host_len_upper, void *out, void *workspace, size_t workspace_bytes,
                           void *stream);
 
-/* y[M][N] = x[M][K] . w[N][K]^T (+ bias[N]) (+ residual[M][N]); x, w, bias, residual: dev elem;
+/* Weight packing.  w: dev elem row-major [N][K]; packed: dev, sf_packed_weight_bytes(ctx,N,K) bytes,
+ * 16-byte aligned.  bf16: 32-row x 16-column units of 1 KiB in the lane order of the 32x32x16 MFMA,
+ * rows and columns zero-padded to multiples of 32 / 16; a prefix of whole 32-row blocks of a packed
+ * matrix is itself a packed matrix (used for the K/V rows of wqkv and the first k slots of W_P). */
+size_t sf_packed_weight_bytes(const sf_ctx *ctx, int32_t N, int32_t K);
+sf_status sf_pack_weight(const sf_ctx *ctx, const void *w, void *packed, int32_t N, int32_t K, void *stream);
+
+/* y[M][N] = x[M][K] . w[N][K]^T (+ bias[N]) (+ residual[M][N]); x, bias, residual: dev elem; w: packed;
  * fp32 accumulation; y: dev elem, or float when out_f32 != 0.  K % 8 == 0, N % 8 == 0.
- * residual may alias y. */
+ * residual may alias y.  workspace (dev, 256-byte aligned, may be NULL): lets skinny shapes split the
+ * K dimension over several workgroups; its first 64 KiB are ticket counters that must be ZERO before
+ * the first use and are left zero by every launch (the same holds for sf_state.workspace, which the
+ * caller zero-fills once after allocating it).  sf_linear_workspace_bytes gives the size to pass. */
+size_t sf_linear_workspace_bytes(const sf_ctx *ctx, int32_t M);
 sf_status sf_op_linear(const sf_ctx *ctx, const void *x, const void *w, const void *bias,
                        const void *residual, void *y, int32_t M, int32_t N, int32_t K, int32_t out_f32,
-                       void *stream);
+                       void *workspace, size_t workspace_bytes, void *stream);
+/* Tuning aid: force the linear kernels' tile configuration (1..7) and split-K factor; 0 = automatic
+ * choice.  Process-wide. host. */
+sf_status sf_tune_linear(int32_t tile, int32_t split_k);
 
 /* RMS normalisation over the last dimension with `n_gain` gain vectors: row r uses gain[r % n_gain]
  * (n_gain = 4 over rows [.,4,d] is the Grouped RMSNorm of the down-sampler).  x, y: dev elem [M][d];

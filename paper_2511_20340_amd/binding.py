@@ -14,7 +14,7 @@ KERNEL_CLASSES = ["linear", "attention", "attention_combine", "rmsnorm", "rope_k
 EXPORTS = [
     "sf_create", "sf_destroy", "sf_workspace_bytes", "sf_kv_cache_bytes", "sf_bind", "sf_draft_step",
     "sf_verify_step", "sf_accept_commit", "sf_kv_import", "sf_kv_export", "sf_attention_workspace_bytes",
-    "sf_op_attention", "sf_op_linear", "sf_op_rmsnorm", "sf_op_rope_kv_append", "sf_op_silu_mul",
+    "sf_op_attention", "sf_packed_weight_bytes", "sf_pack_weight", "sf_linear_workspace_bytes", "sf_op_linear", "sf_tune_linear", "sf_op_rmsnorm", "sf_op_rope_kv_append", "sf_op_silu_mul",
     "sf_argmax_workspace_bytes", "sf_op_argmax", "sf_profile_begin", "sf_profile_end", "sf_strerror", "sf_last_hip_error", "sf_version",
 ]
 
@@ -43,9 +43,10 @@ class State(C.Structure):
 
 
 class SfError(RuntimeError):
-    def __init__(self, status, what):
-        self.status = status
-        super().__init__(f"{what}: {lib().sf_strerror(status).decode()} (status {status})")
+    def __init__(self, status, what, hip_err=0):
+        self.status, self.hip_err = status, hip_err
+        extra = f", hipError_t {hip_err}" if hip_err else ""
+        super().__init__(f"{what}: {lib().sf_strerror(status).decode()} (status {status}{extra})")
 
 
 _lib = None
@@ -59,6 +60,10 @@ def lib():
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_20340_amd.build` "
                            "(or __graft_entry__.build()); there is no CPU fallback")
+    # PyTorch owns the device memory this library works on, and it bundles its own HIP runtime:
+    # load it first so that both sides share ONE libamdhip64 (two runtimes in a process do not
+    # see each other's allocations or streams).
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     P = C.POINTER
     L.sf_create.argtypes = [P(ModelCfg), P(ModelCfg), i32, i32, P(vp)]
@@ -76,7 +81,13 @@ def lib():
     L.sf_attention_workspace_bytes.argtypes = [vp, i32, i32, i32]
     L.sf_attention_workspace_bytes.restype = sz
     L.sf_op_attention.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
-    L.sf_op_linear.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
+    L.sf_op_linear.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]
+    L.sf_packed_weight_bytes.argtypes = [vp, i32, i32]
+    L.sf_packed_weight_bytes.restype = sz
+    L.sf_pack_weight.argtypes = [vp, vp, vp, i32, i32, vp]
+    L.sf_linear_workspace_bytes.argtypes = [vp, i32]
+    L.sf_linear_workspace_bytes.restype = sz
+    L.sf_tune_linear.argtypes = [i32, i32]
     L.sf_op_rmsnorm.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
     L.sf_op_rope_kv_append.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
     L.sf_op_silu_mul.argtypes = [vp, vp, vp, i32, i32, vp]
@@ -97,6 +108,6 @@ def lib():
     return L
 
 
-def check(status, what):
+def check(status, what, ctx=None):
     if status != SF_OK:
-        raise SfError(status, what)
+        raise SfError(status, what, lib().sf_last_hip_error(ctx) if ctx is not None and status == SF_EHIP else 0)

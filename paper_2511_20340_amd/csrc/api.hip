@@ -41,6 +41,7 @@ size_t esize(int dtype) { return dtype == SF_BF16 ? 2 : 4; }
 struct Arena {
   size_t h, a, qkv, qr, ao, gu, act, table, part_o, part_ml, pmax, pidx;  // shared
   size_t f4, x, kvc, xl, s0, dlogits;                                    // draft only
+  size_t gemm_ws, gemm_ws_bytes;
   size_t total;
 };
 
@@ -76,6 +77,8 @@ Arena plan(const sf_ctx *c, int B, int k, int cap) {
   a.xl = take((size_t)B * d * es);
   a.s0 = take(Ms * d * es);
   a.dlogits = take(Ms * V * sizeof(float));
+  a.gemm_ws_bytes = m.dtype == SF_BF16 ? gemm_workspace_bytes((int)Mx) : 0;
+  a.gemm_ws = take(a.gemm_ws_bytes);
   a.total = off;
   return a;
 }
@@ -100,6 +103,10 @@ struct Run {
   const sf_ctx *c;
   hipStream_t s;
   sf_status st = SF_OK;
+  void *gemm_ws = nullptr;
+  size_t gemm_ws_bytes = 0;
+  // a stale error left by an earlier, unrelated HIP call of the process must not be blamed on us
+  Run(const sf_ctx *ctx, hipStream_t stream) : c(ctx), s(stream) { (void)hipGetLastError(); }
   bool ok(hipError_t e) {
     if (st != SF_OK) return false;
     if (e != hipSuccess) { c->hip_err = (int)e; st = SF_EHIP; return false; }
@@ -127,7 +134,7 @@ struct Run {
 void gemm(Run &r, int dtype, const void *x, const void *w, const void *bias, const void *res, void *y, int M, int N,
           int K, int out_f32) {
   if (r.st != SF_OK) return;
-  GemmArgs g{x, w, bias, res, y, M, N, K, out_f32};
+  GemmArgs g{x, w, bias, res, y, M, N, K, out_f32, r.gemm_ws, r.gemm_ws_bytes};
   LAUNCH(K_GEMM, dtype == SF_BF16 ? launch_gemm_bf16(g, r.s) : launch_gemm_f32(g, r.s));
 }
 
@@ -183,7 +190,7 @@ sf_status sf_create(const sf_model_cfg *t, const sf_model_cfg *d, int32_t max_B,
   if (t->n_q_heads % t->n_kv_heads) return SF_EINVAL;
   if (t->dtype != SF_BF16 && t->dtype != SF_F32) return SF_EINVAL;
   if (!(t->rms_eps >= 0.f) || !(t->rope_theta > 1.f)) return SF_EINVAL;
-  if (t->d_model % 8 || t->d_ffn % 8 || (t->n_q_heads * t->head_dim) % 8) return SF_EUNSUPPORTED;
+  if (t->d_model % 8 || t->d_ffn % 8 || (t->n_q_heads * t->head_dim) % 32) return SF_EUNSUPPORTED;
   if (t->dtype == SF_BF16 && t->head_dim != 64 && t->head_dim != 128) return SF_EUNSUPPORTED;
   if (t->dtype == SF_F32 && (t->head_dim % 8 || t->head_dim > 256)) return SF_EUNSUPPORTED;
   sf_status s = check_attn_shape(*t, max_k + 1);
@@ -256,6 +263,7 @@ sf_status sf_verify_step(sf_ctx *c, const sf_state *st, int32_t k, const int32_t
   const int d = m.d_model, F = m.d_ffn, L = m.n_layers;
   const int nq = m.n_q_heads * m.head_dim, nkv = m.n_kv_heads * m.head_dim;
   Run r{c, (hipStream_t)stream};
+  r.gemm_ws = ws + A.gemm_ws; r.gemm_ws_bytes = A.gemm_ws_bytes;
   LAUNCH(K_EMBED_HOOK, launch_embed(c->tw.embed, st->pending, draft, h, st->hooks, B, k, qm, d, m.vocab, m.dtype, r.s));
   RopeArgs ra{};
   ra.qkv = qkv; ra.q_out = qr; ra.kv_len = st->kv_len; ra.n_new = nullptr; ra.table = (float2 *)(ws + A.table);
@@ -306,11 +314,14 @@ sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, 
   const size_t es = esize(m.dtype);
   const sf_draft_weights &w = c->dw;
   Run r{c, (hipStream_t)stream};
+  r.gemm_ws = ws + A.gemm_ws; r.gemm_ws_bytes = A.gemm_ws_bytes;
   // context rows: Grouped RMSNorm -> W_D -> K,V of the draft attention layer at the rows' positions
   norm(r, m, st->hooks, w.group_norm, f4, Mh * 4, 4, 1, qm, qm, nullptr);
   gemm(r, m.dtype, f4, w.w_ds, nullptr, nullptr, x, Mh, d, 4 * d, 0);
   norm(r, m, x, w.attn_norm, a, Mh);
-  gemm(r, m.dtype, a, (const char *)w.wqkv + (size_t)nq * d * es, nullptr, nullptr, kvc, Mh, 2 * nkv, d, 0);
+  // K and V rows of wqkv start after the nq query rows (a whole number of packed 32-row blocks)
+  const size_t kv_off = m.dtype == SF_BF16 ? packed_weight_bytes(nq, d, m.dtype) : (size_t)nq * d * es;
+  gemm(r, m.dtype, a, (const char *)w.wqkv + kv_off, nullptr, nullptr, kvc, Mh, 2 * nkv, d, 0);
   RopeArgs ra{};
   ra.qkv = kvc; ra.q_out = nullptr; ra.kc = st->dk; ra.vc = st->dv; ra.kv_len = st->kv_len; ra.n_new = st->n_new;
   ra.table = (float2 *)(ws + A.table);
@@ -400,12 +411,39 @@ sf_status sf_op_attention(const sf_ctx *c, const void *q, const void *kc, const 
   return r.st;
 }
 
+size_t sf_packed_weight_bytes(const sf_ctx *c, int32_t N, int32_t K) {
+  if (!c || N < 1 || K < 1) return 0;
+  return packed_weight_bytes(N, K, c->tc.dtype);
+}
+
+sf_status sf_pack_weight(const sf_ctx *c, const void *w, void *packed, int32_t N, int32_t K, void *stream) {
+  if (!c || !w || !packed || N < 1 || K < 1) return SF_EINVAL;
+  if (((uintptr_t)packed) % 16) return SF_EINVAL;
+  hipError_t e = launch_pack_weight(w, packed, N, K, c->tc.dtype, (hipStream_t)stream);
+  if (e != hipSuccess) { c->hip_err = (int)e; return SF_EHIP; }
+  return SF_OK;
+}
+
+size_t sf_linear_workspace_bytes(const sf_ctx *c, int32_t M) {
+  if (!c || M < 1 || c->tc.dtype != SF_BF16) return 0;
+  return gemm_workspace_bytes(M);
+}
+
+sf_status sf_tune_linear(int32_t tile, int32_t split_k) {
+  if (tile < 0 || tile > 7 || split_k < 0 || split_k > 64) return SF_EINVAL;
+  gemm_tune(tile, split_k);
+  return SF_OK;
+}
+
 sf_status sf_op_linear(const sf_ctx *c, const void *x, const void *w, const void *bias, const void *residual,
-                       void *y, int32_t M, int32_t N, int32_t K, int32_t out_f32, void *stream) {
+                       void *y, int32_t M, int32_t N, int32_t K, int32_t out_f32, void *workspace,
+                       size_t workspace_bytes, void *stream) {
   if (!c || !x || !w || !y || M < 1 || N < 1 || K < 1) return SF_EINVAL;
   if (K % 8 || N % 8) return SF_EUNSUPPORTED;
   if (((uintptr_t)x | (uintptr_t)w) % 16) return SF_EINVAL;
+  if (workspace && ((uintptr_t)workspace) % ALIGN) return SF_EINVAL;
   Run r{c, (hipStream_t)stream};
+  r.gemm_ws = workspace; r.gemm_ws_bytes = workspace ? workspace_bytes : 0;
   gemm(r, c->tc.dtype, x, w, bias, residual, y, M, N, K, out_f32);
   return r.st;
 }

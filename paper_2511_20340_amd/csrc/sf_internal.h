@@ -88,7 +88,16 @@ struct GemmArgs {
   void *y;
   int M, N, K;
   int out_f32;
+  void *ws;         // split-K tickets (first GEMM_TICKET_BYTES, zero between launches) + partial tiles
+  size_t ws_bytes;  // 0: no split-K
 };
+constexpr size_t GEMM_TICKET_BYTES = 64 * 1024;
+constexpr size_t GEMM_PARTIAL_BYTES = 96u * 1024 * 1024;
+size_t gemm_workspace_bytes(int M_max);
+void gemm_tune(int tile, int split_k);  // tuning overrides, 0 = automatic
+// bf16 weights are consumed in MFMA-operand-packed form (see gemm.hip); fp32 weights stay row-major
+size_t packed_weight_bytes(int N, int K, int dtype);
+hipError_t launch_pack_weight(const void *w, void *packed, int N, int K, int dtype, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmArgs &a, hipStream_t s);
 hipError_t launch_gemm_f32(const GemmArgs &a, hipStream_t s);
 

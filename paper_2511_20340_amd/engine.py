@@ -77,6 +77,24 @@ class Engine:
         self._keep.append(t)
         return t
 
+    def sf_pack_weight(self, w):
+        """row-major device tensor [N,K] -> packed device buffer (kept alive by the engine)."""
+        N, K = w.shape
+        nb = self.lib.sf_packed_weight_bytes(self.ctx, N, K)
+        es = 2 if self.dtype_id == sfb.SF_BF16 else 4
+        out = torch.empty(nb // es, dtype=self.tdtype, device=self.dev)
+        sfb.check(self.lib.sf_pack_weight(self.ctx, _ptr(w), _ptr(out), N, K, _stream()), "sf_pack_weight")
+        self._keep.append(out)
+        return out
+
+    def _lin(self, a):
+        """upload + pack one linear weight; the row-major copy is dropped."""
+        t = self._up(a)
+        self._keep.pop()
+        p = self.sf_pack_weight(t)
+        torch.cuda.current_stream().synchronize()
+        return p
+
     def bind(self, tw, dw=None):
         """tw / dw: dicts of arrays (numpy float32 or torch) named as in the C structs; a dict that
         has separate w_gate / w_up gets them stacked into w_gate_up = [gate; up]."""
@@ -85,18 +103,20 @@ class Engine:
 
         def gate_up(w, l=None):
             if "w_gate_up" in w:
-                return self._up(w["w_gate_up"] if l is None else w["w_gate_up"][l])
+                return self._lin(w["w_gate_up"] if l is None else w["w_gate_up"][l])
             g, u = (w["w_gate"], w["w_up"]) if l is None else (w["w_gate"][l], w["w_up"][l])
             g, u = (torch.as_tensor(np.asarray(g)) if not isinstance(g, torch.Tensor) else g,
                     torch.as_tensor(np.asarray(u)) if not isinstance(u, torch.Tensor) else u)
-            return self._up(torch.cat([g, u], 0))
+            return self._lin(torch.cat([g, u], 0))
         T = sfb.TargetWeights()
         self.w = {}
         for n in ("embed", "lm_head", "final_norm"):
-            self.w[n] = self._up(tw[n])
+            self.w[n] = self._lin(tw[n]) if n == "lm_head" else self._up(tw[n])
             setattr(T, n, self.w[n].data_ptr())
-        for n in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_down"):
+        for n in ("attn_norm", "ffn_norm"):
             self.w[n] = [self._up(tw[n][l]) for l in range(L)]
+        for n in ("wqkv", "wo", "w_down"):
+            self.w[n] = [self._lin(tw[n][l]) for l in range(L)]
         self.w["w_gate_up"] = [gate_up(tw, l) for l in range(L)]
         for n in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down"):
             arr = (C.c_void_p * L)(*[t.data_ptr() for t in self.w[n]])
@@ -107,7 +127,12 @@ class Engine:
             D = sfb.DraftWeights()
             self.wd = {}
             for n, _ in sfb.DraftWeights._fields_:
-                self.wd[n] = gate_up(dw) if n == "w_gate_up" else self._up(dw[n])
+                if n == "w_gate_up":
+                    self.wd[n] = gate_up(dw)
+                elif n in ("w_ds", "w_pos", "wqkv", "wo", "w_down"):
+                    self.wd[n] = self._lin(dw[n])
+                else:
+                    self.wd[n] = self._up(dw[n])
                 setattr(D, n, self.wd[n].data_ptr())
         self._T, self._D = T, D
         sfb.check(self.lib.sf_bind(self.ctx, C.byref(T), C.byref(D) if D is not None else None), "sf_bind")
@@ -116,14 +141,14 @@ class Engine:
     def sf_draft_step(self, k, mask=sfb.SF_MASK_BIDIR, draft_out=None, logits_out=None):
         out = draft_out if draft_out is not None else torch.empty(self.B, max(k, 0), dtype=torch.int32, device=self.dev)
         sfb.check(self.lib.sf_draft_step(self.ctx, C.byref(self.st), k, mask, self.len_upper, _ptr(out),
-                                         _ptr(logits_out), _stream()), "sf_draft_step")
+                                         _ptr(logits_out), _stream()), "sf_draft_step", self.ctx)
         return out
 
     def sf_verify_step(self, k, draft, logits_out=None):
         lg = logits_out if logits_out is not None else \
             torch.empty(self.B, k + 1, self.V, dtype=torch.float32, device=self.dev)
         sfb.check(self.lib.sf_verify_step(self.ctx, C.byref(self.st), k, _ptr(draft) if k > 0 else None,
-                                          self.len_upper, _ptr(lg), _stream()), "sf_verify_step")
+                                          self.len_upper, _ptr(lg), _stream()), "sf_verify_step", self.ctx)
         return lg
 
     def sf_accept_commit(self, k, draft, logits, force_len=None, accept_out=None, tokens_out=None):
@@ -132,7 +157,7 @@ class Engine:
             torch.empty(self.B, k + 1, dtype=torch.int32, device=self.dev)
         sfb.check(self.lib.sf_accept_commit(self.ctx, C.byref(self.st), k, _ptr(draft) if k > 0 else None,
                                             _ptr(logits), _ptr(force_len), _ptr(acc), _ptr(out), _stream()),
-                  "sf_accept_commit")
+                  "sf_accept_commit", self.ctx)
         self.len_upper = min(self.len_upper + k + 1, self.cap)
         return acc, out
 
@@ -191,16 +216,34 @@ class Engine:
         out = torch.empty_like(q)
         sfb.check(self.lib.sf_op_attention(self.ctx, _ptr(q), _ptr(kc), _ptr(vc), _ptr(kv_len), B, n_q, self.cap,
                                            mask, len_upper, _ptr(out), C.c_void_p(p), need, _stream()),
-                  "sf_op_attention")
+                  "sf_op_attention", self.ctx)
         self._keep_ws = ws
         return out
 
-    def sf_op_linear(self, x, w, bias=None, residual=None, out_f32=False):
+    def linear_workspace(self, M):
+        """(pointer, bytes) of a zero-filled split-K workspace, cached per engine."""
+        nb = self.lib.sf_linear_workspace_bytes(self.ctx, M)
+        if nb == 0:
+            return None, 0
+        if getattr(self, "_lin_ws", None) is None or self._lin_ws.numel() < nb + 256:
+            self._lin_ws = torch.zeros(nb + 256, dtype=torch.uint8, device=self.dev)
+        p = self._lin_ws.data_ptr() + (-self._lin_ws.data_ptr()) % 256
+        return C.c_void_p(p), nb
+
+    def sf_op_linear(self, x, w, bias=None, residual=None, out_f32=False, y=None, packed=None):
+        """w: row-major [N,K] device tensor (packed here) unless `packed` = (buffer, N) is given."""
         M, K = x.shape
-        N = w.shape[0]
-        y = torch.empty(M, N, dtype=torch.float32 if out_f32 else self.tdtype, device=self.dev)
+        if packed is None:
+            N = w.shape[0]
+            w = self.sf_pack_weight(w)
+            self._keep.pop()
+        else:
+            w, N = packed
+        if y is None:
+            y = torch.empty(M, N, dtype=torch.float32 if out_f32 else self.tdtype, device=self.dev)
+        wsp, nb = self.linear_workspace(M)
         sfb.check(self.lib.sf_op_linear(self.ctx, _ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(y), M, N, K,
-                                        int(out_f32), _stream()), "sf_op_linear")
+                                        int(out_f32), wsp, nb, _stream()), "sf_op_linear", self.ctx)
         return y
 
     def sf_op_rmsnorm(self, x, gain, n_gain=1):
