@@ -191,7 +191,11 @@ def main():
     logits = torch.empty(B, k + 1, m.vocab, dtype=torch.float32, device="cuda")
     toks = torch.empty(B, k + 1, dtype=torch.int32, device="cuda")
 
-    def run(n, calibrated, acc_hist=None, len_hist=None, phase_ev=None):
+    tok_hist = torch.full((2 * (steps + warm) + 4, B, k + 1), -1, dtype=torch.int32, device="cuda")
+    tok_pos = torch.zeros(2 * (steps + warm) + 4, B, dtype=torch.int64, device="cuda")
+    hist_i = [0]
+
+    def run(n, calibrated, acc_hist=None, len_hist=None, phase_ev=None, record=False):
         for i in range(n):
             if phase_ev is not None:
                 phase_ev[i][0].record()
@@ -206,23 +210,37 @@ def main():
             eng.sf_verify_step(k, draft, logits_out=logits)
             if phase_ev is not None:
                 phase_ev[i][2].record()
+            if record:   # where in the plain-greedy stream this step's first output token belongs
+                tok_pos[hist_i[0]].copy_(eng.kv_len.to(torch.int64) - len_t + 1)
             eng.sf_accept_commit(k, draft, logits, accept_out=None if acc_hist is None else acc_hist[i],
-                                 tokens_out=toks)
+                                 tokens_out=tok_hist[hist_i[0]] if record else toks)
+            if record:
+                hist_i[0] += 1
             if phase_ev is not None:
                 phase_ev[i][3].record()
 
     def timed_pass(calibrated):
-        run(warm, calibrated)
+        run(warm, calibrated, record=True)
         acc = torch.zeros(steps, B, dtype=torch.int32, device="cuda")
         torch.cuda.synchronize()
         t = time.perf_counter()
-        run(steps, calibrated, acc_hist=acc)
+        run(steps, calibrated, acc_hist=acc, record=True)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t
         return dt, int(acc.sum().item())
 
     dt_nat, tok_nat = timed_pass(False)
     dt_cal, tok_cal = timed_pass(True)
+
+    # lossless property at full size: every token the speculative path emitted equals the target's
+    # own plain-greedy continuation at that place of the stream
+    nrec = hist_i[0]
+    pos = tok_pos[:nrec, :, None] + torch.arange(k + 1, device="cuda")[None, None, :]
+    want = torch.gather(ar.to(torch.int64)[None].expand(nrec, B, n_ar), 2, pos.clamp(max=n_ar - 1))
+    got = tok_hist[:nrec].to(torch.int64)
+    emitted = got >= 0
+    lossless = {"tokens_compared": int(emitted.sum().item()),
+                "mismatches": int(((got != want) & emitted).sum().item())}
 
     result = {
         "metric": "accepted tokens/s at batch B (draft+verify+accept step)",
@@ -235,6 +253,7 @@ def main():
                    "vocab": m.vocab, "drafts": "natural (the random-init draft block's own tokens)",
                    "state": "real chunked prefill through sf_verify_step", "prefill_s": round(t_prefill, 3)},
         "kappa": tok_nat / (steps * B),
+        "lossless_check": lossless,
         "step_us": 1e6 * dt_nat / steps,
         "calibrated": {"what": "draft tokens replaced after sf_draft_step by the target's greedy continuation, "
                                "each slot corrupted with probability 1-alpha, so kappa matches the paper's model class",

@@ -56,6 +56,10 @@ Arena plan(const sf_ctx *c, int B, int k, int cap) {
   Arena a;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += up(bytes); return o; };
+  // first, at an offset that does not depend on k: the split-K ticket counters must stay zero
+  // between calls, so no other buffer of any call shape may ever overlap them
+  a.gemm_ws_bytes = m.dtype == SF_BF16 ? gemm_workspace_bytes((int)Mx) : 0;
+  a.gemm_ws = take(a.gemm_ws_bytes);
   a.h = take(M * d * es);
   a.a = take(Mx * d * es);
   a.qkv = take(M * (nq + 2 * nkv) * es);
@@ -77,8 +81,6 @@ Arena plan(const sf_ctx *c, int B, int k, int cap) {
   a.xl = take((size_t)B * d * es);
   a.s0 = take(Ms * d * es);
   a.dlogits = take(Ms * V * sizeof(float));
-  a.gemm_ws_bytes = m.dtype == SF_BF16 ? gemm_workspace_bytes((int)Mx) : 0;
-  a.gemm_ws = take(a.gemm_ws_bytes);
   a.total = off;
   return a;
 }

@@ -272,3 +272,33 @@ def test_lossless_on_the_gpu(name):
             assert np.all(accs == 1)
         if fn is mostly_right:
             assert accs.max() > 1
+
+
+def test_one_engine_switching_between_k0_and_k4():
+    """Plain greedy steps (k = 0) and speculative steps (k = 4) issued through the SAME engine and
+    workspace give bit-identical logits for the same rows (the workspace layout depends on k; the
+    split-K ticket counters must survive that), and verify-block rows equal the step-by-step rows."""
+    m = SLICES["8b-slice"]
+    B, k, seed, cap = 6, 4, 21, 160
+    lens = [40, 77, 12, 64, 100, 33]
+    prompts = synth.prompts(lens, m.vocab, seed)
+    _, eng, _, _ = make_pair(m, B, cap, k, seed, std=0.05)
+    eng.prefill(prompts)
+    snap = {n: getattr(eng, n).clone() for n in ("kv_len", "pending", "n_new", "cu_new", "hooks")}
+    len0 = eng.len_upper
+    none = torch.zeros(B, 0, dtype=torch.int32, device="cuda")
+    toks, rows = [eng.pending.clone()], []
+    for _ in range(k + 1):
+        lg = eng.sf_verify_step(0, none)
+        rows.append(lg[:, 0].clone())
+        _, out = eng.sf_accept_commit(0, none, lg)
+        toks.append(out[:, 0].clone())
+    for n, t in snap.items():
+        getattr(eng, n).copy_(t)
+    eng.len_upper = len0
+    draft = torch.stack(toks[1:k + 1], 1).contiguous()
+    lg = eng.sf_verify_step(k, draft)
+    for i in range(k + 1):
+        assert torch.equal(lg[:, i], rows[i]), i
+    acc, _ = eng.sf_accept_commit(k, draft, lg)
+    assert acc.cpu().tolist() == [k + 1] * B
