@@ -73,7 +73,7 @@ typedef struct {
   const void *const *wqkv;        /* L x [(Hq+2Hkv)*hd][d]  rows: Q heads, K heads, V heads */
   const void *const *wo;          /* L x [d][Hq*hd]                                */
   const void *const *ffn_norm;    /* L x [d]                                       */
-  const void *const *w_gate_up;   /* L x [2F][d]  rows [0,F) gate, rows [F,2F) up  */
+  const void *const *w_gate_up;   /* L x [2F][d]  rows [0,F) gate, [F,2F) up; packed with glu=1 */
   const void *const *w_down;      /* L x [d][F]                                    */
 } sf_target_weights;
 
@@ -88,7 +88,7 @@ typedef struct {
   const void *wqkv;       /* [(Hq+2Hkv)*hd][d]                                                     */
   const void *wo;         /* [d][Hq*hd]                                                            */
   const void *ffn_norm;   /* [d]                                                                   */
-  const void *w_gate_up;  /* [2F][d]                                                               */
+  const void *w_gate_up;  /* [2F][d]  packed with glu = 1                                          */
   const void *w_down;     /* [d][F]                                                                */
   const void *out_norm;   /* [d]  the draft's own output norm; logits use the target's lm_head     */
 } sf_draft_weights;
@@ -190,9 +190,12 @@ sf_status sf_op_attention(const sf_ctx *ctx, const void *q, const void *kc, cons
 /* Weight packing.  w: dev elem row-major [N][K]; packed: dev, sf_packed_weight_bytes(ctx,N,K) bytes,
  * 16-byte aligned.  bf16: 32-row x 16-column units of 1 KiB in the lane order of the 32x32x16 MFMA,
  * rows and columns zero-padded to multiples of 32 / 16; a prefix of whole 32-row blocks of a packed
- * matrix is itself a packed matrix (used for the K/V rows of wqkv and the first k slots of W_P). */
+ * matrix is itself a packed matrix (used for the K/V rows of wqkv and the first k slots of W_P).
+ * glu != 0 (only for w_gate_up = [gate; up], N = 2F, F % 32 == 0): gate and up rows are interleaved 16 by
+ * 16 so that the linear kernel's epilogue can form silu(gate)*up in registers. */
 size_t sf_packed_weight_bytes(const sf_ctx *ctx, int32_t N, int32_t K);
-sf_status sf_pack_weight(const sf_ctx *ctx, const void *w, void *packed, int32_t N, int32_t K, void *stream);
+sf_status sf_pack_weight(const sf_ctx *ctx, const void *w, void *packed, int32_t N, int32_t K, int32_t glu,
+                         void *stream);
 
 /* y[M][N] = x[M][K] . w[N][K]^T (+ bias[N]) (+ residual[M][N]); x, bias, residual: dev elem; w: packed;
  * fp32 accumulation; y: dev elem, or float when out_f32 != 0.  K % 8 == 0, N % 8 == 0.
@@ -204,9 +207,15 @@ size_t sf_linear_workspace_bytes(const sf_ctx *ctx, int32_t M);
 sf_status sf_op_linear(const sf_ctx *ctx, const void *x, const void *w, const void *bias,
                        const void *residual, void *y, int32_t M, int32_t N, int32_t K, int32_t out_f32,
                        void *workspace, size_t workspace_bytes, void *stream);
+/* SwiGLU input half: act[M][F] = silu(x . Wg^T) * (x . Wu^T); w_gate_up packed with glu = 1 (SF_BF16:
+ * one kernel, gate/up never leave registers; SF_F32: workspace must hold M*2F floats). act: dev elem. */
+sf_status sf_op_linear_swiglu(const sf_ctx *ctx, const void *x, const void *w_gate_up, void *act, int32_t M,
+                              int32_t F, int32_t K, void *workspace, size_t workspace_bytes, void *stream);
 /* Tuning aid: force the linear kernels' tile configuration (1..7) and split-K factor; 0 = automatic
  * choice.  Process-wide. host. */
 sf_status sf_tune_linear(int32_t tile, int32_t split_k);
+/* Tuning aid: force the attention's split-KV chunk size in 32-key tiles (>= 16); 0 = automatic. host. */
+sf_status sf_tune_attention(int32_t chunk_tiles);
 
 /* RMS normalisation over the last dimension with `n_gain` gain vectors: row r uses gain[r % n_gain]
  * (n_gain = 4 over rows [.,4,d] is the Grouped RMSNorm of the down-sampler).  x, y: dev elem [M][d];

@@ -134,10 +134,21 @@ struct Run {
 #define LAUNCH(cls, expr) r.launch(cls, [&] { return (expr); })
 
 void gemm(Run &r, int dtype, const void *x, const void *w, const void *bias, const void *res, void *y, int M, int N,
-          int K, int out_f32) {
+          int K, int out_f32, int glu = 0) {
   if (r.st != SF_OK) return;
-  GemmArgs g{x, w, bias, res, y, M, N, K, out_f32, r.gemm_ws, r.gemm_ws_bytes};
+  GemmArgs g{x, w, bias, res, y, M, N, K, out_f32, glu, r.gemm_ws, r.gemm_ws_bytes};
   LAUNCH(K_GEMM, dtype == SF_BF16 ? launch_gemm_bf16(g, r.s) : launch_gemm_f32(g, r.s));
+}
+
+// act[M][F] = silu(a . Wg^T) * (a . Wu^T): one kernel in bf16 mode (weight packed with glu = 1), GEMM to
+// fp32 + gating kernel in fp32 mode
+void swiglu_in(Run &r, int dtype, const void *a, const void *w_gate_up, float *gu, void *act, int M, int F, int K) {
+  if (dtype == SF_BF16) {
+    gemm(r, dtype, a, w_gate_up, nullptr, nullptr, act, M, 2 * F, K, 0, 1);
+  } else {
+    gemm(r, dtype, a, w_gate_up, nullptr, nullptr, gu, M, 2 * F, K, 1);
+    LAUNCH(K_SILU, launch_silu_mul(gu, act, M, F, dtype, r.s));
+  }
 }
 
 void norm(Run &r, const sf_model_cfg &m, const void *x, const void *gain, void *y, int M, int n_gain = 1,
@@ -154,7 +165,8 @@ void attention(Run &r, const sf_model_cfg &m, const void *q, const void *kc, con
   a.q = q; a.kc = kc; a.vc = vc; a.kv_len = kv_len; a.out = out; a.part_o = part_o; a.part_ml = part_ml;
   a.B = B; a.n_q = n_q; a.Hq = m.n_q_heads; a.Hkv = m.n_kv_heads; a.hd = m.head_dim; a.cap = cap; a.mode = mode;
   a.len_upper = len_upper;
-  a.chunk_tiles = attn_chunk_tiles(len_upper, n_q);
+  const int n_rt = (m.n_q_heads / m.n_kv_heads * n_q + 31) / 32;
+  a.chunk_tiles = attn_chunk_tiles(B * m.n_kv_heads * n_rt, len_upper + n_q);
   const int n_tiles = (len_upper + n_q + TK - 1) / TK;
   a.n_chunks = (n_tiles + a.chunk_tiles - 1) / a.chunk_tiles;
   LAUNCH(K_ATTN, m.dtype == SF_BF16 ? launch_attention_bf16(a, r.s) : launch_attention_f32(a, r.s));
@@ -192,7 +204,7 @@ sf_status sf_create(const sf_model_cfg *t, const sf_model_cfg *d, int32_t max_B,
   if (t->n_q_heads % t->n_kv_heads) return SF_EINVAL;
   if (t->dtype != SF_BF16 && t->dtype != SF_F32) return SF_EINVAL;
   if (!(t->rms_eps >= 0.f) || !(t->rope_theta > 1.f)) return SF_EINVAL;
-  if (t->d_model % 8 || t->d_ffn % 8 || (t->n_q_heads * t->head_dim) % 32) return SF_EUNSUPPORTED;
+  if (t->d_model % 8 || t->d_ffn % 32 || (t->n_q_heads * t->head_dim) % 32) return SF_EUNSUPPORTED;
   if (t->dtype == SF_BF16 && t->head_dim != 64 && t->head_dim != 128) return SF_EUNSUPPORTED;
   if (t->dtype == SF_F32 && (t->head_dim % 8 || t->head_dim > 256)) return SF_EUNSUPPORTED;
   sf_status s = check_attn_shape(*t, max_k + 1);
@@ -287,8 +299,7 @@ sf_status sf_verify_step(sf_ctx *c, const sf_state *st, int32_t k, const int32_t
               SF_MASK_CAUSAL, len_upper);
     gemm(r, m.dtype, ao, c->wo[l], nullptr, h, h, M, d, nq, 0);
     norm(r, m, h, c->ffn_norm[l], a, M);
-    gemm(r, m.dtype, a, c->w_gate_up[l], nullptr, nullptr, gu, M, 2 * F, d, 1);
-    LAUNCH(K_SILU, launch_silu_mul(gu, act, M, F, m.dtype, r.s));
+    swiglu_in(r, m.dtype, a, c->w_gate_up[l], gu, act, M, F, d);
     gemm(r, m.dtype, act, c->w_down[l], nullptr, h, h, M, d, F, 0);
   }
   norm(r, m, h, c->tw.final_norm, a, M);
@@ -344,8 +355,7 @@ sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, 
             cap, mask, len_upper);
   gemm(r, m.dtype, ao, w.wo, nullptr, s0, s0, Ms, d, nq, 0);
   norm(r, m, s0, w.ffn_norm, a, Ms);
-  gemm(r, m.dtype, a, w.w_gate_up, nullptr, nullptr, gu, Ms, 2 * F, d, 1);
-  LAUNCH(K_SILU, launch_silu_mul(gu, act, Ms, F, m.dtype, r.s));
+  swiglu_in(r, m.dtype, a, w.w_gate_up, gu, act, Ms, F, d);
   gemm(r, m.dtype, act, w.w_down, nullptr, s0, s0, Ms, d, F, 0);
   norm(r, m, s0, w.out_norm, a, Ms);
   gemm(r, m.dtype, a, c->tw.lm_head, nullptr, nullptr, dlogits, Ms, m.vocab, d, 1);
@@ -418,10 +428,12 @@ size_t sf_packed_weight_bytes(const sf_ctx *c, int32_t N, int32_t K) {
   return packed_weight_bytes(N, K, c->tc.dtype);
 }
 
-sf_status sf_pack_weight(const sf_ctx *c, const void *w, void *packed, int32_t N, int32_t K, void *stream) {
+sf_status sf_pack_weight(const sf_ctx *c, const void *w, void *packed, int32_t N, int32_t K, int32_t glu,
+                         void *stream) {
   if (!c || !w || !packed || N < 1 || K < 1) return SF_EINVAL;
   if (((uintptr_t)packed) % 16) return SF_EINVAL;
-  hipError_t e = launch_pack_weight(w, packed, N, K, c->tc.dtype, (hipStream_t)stream);
+  if (glu && (N % 64)) return SF_EUNSUPPORTED;  // F = N/2 must be a multiple of 32
+  hipError_t e = launch_pack_weight(w, packed, N, K, glu, c->tc.dtype, (hipStream_t)stream);
   if (e != hipSuccess) { c->hip_err = (int)e; return SF_EHIP; }
   return SF_OK;
 }
@@ -429,6 +441,12 @@ sf_status sf_pack_weight(const sf_ctx *c, const void *w, void *packed, int32_t N
 size_t sf_linear_workspace_bytes(const sf_ctx *c, int32_t M) {
   if (!c || M < 1 || c->tc.dtype != SF_BF16) return 0;
   return gemm_workspace_bytes(M);
+}
+
+sf_status sf_tune_attention(int32_t chunk_tiles) {
+  if (chunk_tiles < 0 || (chunk_tiles > 0 && chunk_tiles < 16)) return SF_EINVAL;
+  attn_tune(chunk_tiles);
+  return SF_OK;
 }
 
 sf_status sf_tune_linear(int32_t tile, int32_t split_k) {
@@ -447,6 +465,20 @@ sf_status sf_op_linear(const sf_ctx *c, const void *x, const void *w, const void
   Run r{c, (hipStream_t)stream};
   r.gemm_ws = workspace; r.gemm_ws_bytes = workspace ? workspace_bytes : 0;
   gemm(r, c->tc.dtype, x, w, bias, residual, y, M, N, K, out_f32);
+  return r.st;
+}
+
+sf_status sf_op_linear_swiglu(const sf_ctx *c, const void *x, const void *w_gate_up, void *act, int32_t M, int32_t F,
+                              int32_t K, void *workspace, size_t workspace_bytes, void *stream) {
+  if (!c || !x || !w_gate_up || !act || M < 1 || F < 1 || K < 1) return SF_EINVAL;
+  if (K % 8 || F % 32) return SF_EUNSUPPORTED;
+  if (workspace && ((uintptr_t)workspace) % ALIGN) return SF_EINVAL;
+  const bool bf = c->tc.dtype == SF_BF16;
+  const size_t lin = bf ? gemm_workspace_bytes(M) : 0, gu_bytes = bf ? 0 : up((size_t)M * 2 * F * sizeof(float));
+  if (!bf && (!workspace || workspace_bytes < gu_bytes)) return SF_ECAPACITY;
+  Run r{c, (hipStream_t)stream};
+  if (bf && workspace && workspace_bytes >= lin) { r.gemm_ws = workspace; r.gemm_ws_bytes = workspace_bytes; }
+  swiglu_in(r, c->tc.dtype, x, w_gate_up, (float *)workspace, act, M, F, K);
   return r.st;
 }
 

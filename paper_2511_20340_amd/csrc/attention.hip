@@ -321,16 +321,25 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
 
 }  // namespace
 
-// Chunk size: the grid is sized from the host's upper bound of the lengths.  Aim at roughly
-// 4 workgroups per CU in flight and at least 4 tiles per wave (16 per workgroup).
-int attn_chunk_tiles(int len_upper, int n_q) {
-  (void)len_upper; (void)n_q;
-  return 16;
+namespace { int g_chunk_tiles = 0; }
+void attn_tune(int chunk_tiles) { g_chunk_tiles = chunk_tiles; }
+
+// Chunk size (in 32-key tiles) of the split-KV decomposition.  The grid is sized from the host's
+// upper bound of the lengths: split only when there are fewer (sequence, head, row tile) groups
+// than CUs, and never below 16 tiles (4 per wave) per chunk; with >= 256 groups every group is one
+// workgroup and no combine pass is needed (measured fastest at every batch >= 32).
+int attn_chunk_tiles(int groups, int keys_upper) {
+  if (g_chunk_tiles > 0) return g_chunk_tiles;
+  const int n_tiles = (keys_upper + TK - 1) / TK;
+  const int want_chunks = (256 + groups - 1) / (groups > 0 ? groups : 1);
+  int ct = (n_tiles + want_chunks - 1) / want_chunks;
+  return ct < 16 ? 16 : ct;
 }
 
 size_t attn_workspace_bytes(int B, int Hkv, int hd, int G, int n_q, int len_upper) {
   const int n_rt = (G * n_q + 31) / 32;
-  const int ct = attn_chunk_tiles(len_upper, n_q);
+  // sized for the smallest chunk any launch may pick (16 tiles)
+  const int ct = 16;
   const int n_tiles = (len_upper + n_q + TK - 1) / TK;
   const int n_chunks = (n_tiles + ct - 1) / ct;
   if (n_chunks <= 1) return 0;

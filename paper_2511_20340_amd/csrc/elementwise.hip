@@ -16,12 +16,41 @@ __device__ __forceinline__ float block_sum_256(float v, float *red) {
   return t;
 }
 
+// 16-byte vector access to a row of T: VEC elements per access
+template <typename T> struct Vec;
+template <> struct Vec<bf16_t> {
+  static constexpr int N = 8;
+  static __device__ __forceinline__ void ld(const bf16_t *p, float (&v)[8]) {
+    const uint4 u = *reinterpret_cast<const uint4 *>(p);
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[2 * i] = __uint_as_float(w[i] << 16); v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u); }
+  }
+  static __device__ __forceinline__ void st(bf16_t *p, const float (&v)[8]) {
+    *reinterpret_cast<uint4 *>(p) = make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]),
+                                               pack2bf(v[6], v[7]));
+  }
+};
+template <> struct Vec<float> {
+  static constexpr int N = 4;
+  static __device__ __forceinline__ void ld(const float *p, float (&v)[4]) {
+    const float4 u = *reinterpret_cast<const float4 *>(p);
+    v[0] = u.x; v[1] = u.y; v[2] = u.z; v[3] = u.w;
+  }
+  static __device__ __forceinline__ void st(float *p, const float (&v)[4]) {
+    *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  }
+};
+
 // One workgroup per output row.  y = gain[r % n_gain] * x / sqrt(mean(x^2) + eps).
+// The row stays in registers between the two passes (up to 4 x 16 bytes per thread, i.e.
+// d <= 8192 bf16 / 4096 fp32); longer or unaligned rows take the scalar path.
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *__restrict__ X, const T *__restrict__ gain,
                                                       T *__restrict__ Y, int d, int n_gain, float eps, int map,
                                                       int q, int q_max, const int32_t *__restrict__ n_new) {
   __shared__ float red[4];
+  constexpr int VN = Vec<T>::N;
   const int r = blockIdx.x;
   long in_row = r;
   bool zero = false;
@@ -36,6 +65,36 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *__restrict__ X, c
   const T *x = X + in_row * d;
   const T *gv = gain + (size_t)(r % n_gain) * d;
   T *y = Y + (size_t)r * d;
+  if (d % VN == 0 && d <= VN * 256 * 4) {
+    float v[4][VN];
+    float ss = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int e = (threadIdx.x + 256 * j) * VN;
+      if (e < d && !zero) {
+        Vec<T>::ld(x + e, v[j]);
+#pragma unroll
+        for (int i = 0; i < VN; ++i) ss += v[j][i] * v[j][i];
+      } else {
+#pragma unroll
+        for (int i = 0; i < VN; ++i) v[j][i] = 0.f;
+      }
+    }
+    ss = block_sum_256(ss, red);
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int e = (threadIdx.x + 256 * j) * VN;
+      if (e < d) {
+        float g[VN], o[VN];
+        Vec<T>::ld(gv + e, g);
+#pragma unroll
+        for (int i = 0; i < VN; ++i) o[i] = g[i] * (v[j][i] * inv);
+        Vec<T>::st(y + e, o);
+      }
+    }
+    return;
+  }
   float ss = 0.f;
   if (!zero)
     for (int e = threadIdx.x; e < d; e += 256) {

@@ -33,7 +33,8 @@ __global__ __launch_bounds__(256, OCC) void gemm_wd_kernel(const bf16_t *__restr
                                                       const bf16_t *__restrict__ bias, const bf16_t *residual,
                                                       void *Y, int M, int N, int K, int out_f32, int tiles_m,
                                                       int tiles_n, int split_k, int kt_per_split,
-                                                      float *__restrict__ partial, unsigned *__restrict__ tickets) {
+                                                      float *__restrict__ partial, unsigned *__restrict__ tickets,
+                                                      int glu) {
   constexpr int BM = TM * 32;
   extern __shared__ __attribute__((aligned(16))) bf16_t sA[];  // [2][BM][LDK]
   __shared__ unsigned s_ticket;
@@ -167,6 +168,30 @@ __global__ __launch_bounds__(256, OCC) void gemm_wd_kernel(const bf16_t *__restr
     if (tid == 0) __hip_atomic_store(&tickets[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 
+  if (glu) {
+    // SwiGLU epilogue.  The weight was packed with gate and up rows interleaved 16 by 16, so a
+    // 32-column tile holds gate features f..f+15 in columns 0-15 and the matching up features in
+    // columns 16-31: lane ln < 16 fetches its partner's value and writes silu(gate) * up.
+    const int F = N >> 1;
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+      for (int b = 0; b < TN; ++b) {
+        const int col = (nb0 + b) * 16 + (ln & 15);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float mine = acc[a][b][v];
+          const float other = __shfl_xor(mine, 16);
+          const int row = m0 + a * 32 + c_row(v, lh);
+          if ((ln & 16) == 0 && col < F && row < M) {
+            const float r = mine / (1.0f + __expf(-mine)) * other;
+            reinterpret_cast<bf16_t *>(Y)[(size_t)row * F + col] = f2bf(r);
+          }
+        }
+      }
+    return;
+  }
+
   // epilogue: lane holds column ln, rows c_row(v, lh) of every 32x32 tile
 #pragma unroll
   for (int a = 0; a < TM; ++a)
@@ -189,7 +214,10 @@ __global__ __launch_bounds__(256, OCC) void gemm_wd_kernel(const bf16_t *__restr
 }
 
 // row-major [N][K] -> packed units; one thread per 16-byte operand register
-__global__ void pack_weight_kernel(const bf16_t *__restrict__ W, uint4 *__restrict__ P, int N, int K, size_t units) {
+// glu_F > 0: W is [2F][K] = [gate; up] and packed row block nb holds gate rows 16nb..16nb+15 followed
+// by up rows 16nb..16nb+15 (see the SwiGLU epilogue)
+__global__ void pack_weight_kernel(const bf16_t *__restrict__ W, uint4 *__restrict__ P, int N, int K, size_t units,
+                                   int glu_F) {
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= units) return;
   const int lane = idx & 63;
@@ -197,7 +225,12 @@ __global__ void pack_weight_kernel(const bf16_t *__restrict__ W, uint4 *__restri
   const int k_steps = (K + 15) >> 4;
   const int kstep = u % k_steps;
   const int nb = u / k_steps;
-  const int row = nb * 32 + (lane & 31), k0 = kstep * 16 + (lane >> 5) * 8;
+  int row = nb * 32 + (lane & 31);
+  const int k0 = kstep * 16 + (lane >> 5) * 8;
+  if (glu_F > 0) {
+    const int within = lane & 31, f = nb * 16 + (within & 15);
+    row = f < glu_F ? (within < 16 ? f : glu_F + f) : N;
+  }
   uint32_t w[4] = {0, 0, 0, 0};
   if (row < N)
     for (int e = 0; e < 8; ++e)
@@ -257,7 +290,7 @@ hipError_t run_wd(const GemmArgs &a, hipStream_t s, int split_req) {
   float *partial = a.ws ? (float *)((char *)a.ws + GEMM_TICKET_BYTES) : nullptr;
   kern<<<dim3(groups * XCDS * p.tiles_m * p.split_k), dim3(256), lds, s>>>(
       (const bf16_t *)a.x, (const uint4 *)a.w, (const bf16_t *)a.bias, (const bf16_t *)a.residual, a.y, a.M, a.N,
-      a.K, a.out_f32, p.tiles_m, p.tiles_n, p.split_k, p.kt_per_split, partial, tickets);
+      a.K, a.out_f32, p.tiles_m, p.tiles_n, p.split_k, p.kt_per_split, partial, tickets, a.glu);
   return hipGetLastError();
 }
 
@@ -317,10 +350,11 @@ size_t packed_weight_bytes(int N, int K, int dtype) {
   return (size_t)((N + 31) / 32) * ((K + 15) / 16) * 1024;
 }
 
-hipError_t launch_pack_weight(const void *w, void *packed, int N, int K, int dtype, hipStream_t s) {
+hipError_t launch_pack_weight(const void *w, void *packed, int N, int K, int glu, int dtype, hipStream_t s) {
   if (dtype != SF_BF16) return hipMemcpyAsync(packed, w, (size_t)N * K * sizeof(float), hipMemcpyDeviceToDevice, s);
   const size_t units = packed_weight_bytes(N, K, dtype) / 16;
-  pack_weight_kernel<<<(unsigned)((units + 255) / 256), 256, 0, s>>>((const bf16_t *)w, (uint4 *)packed, N, K, units);
+  pack_weight_kernel<<<(unsigned)((units + 255) / 256), 256, 0, s>>>((const bf16_t *)w, (uint4 *)packed, N, K, units,
+                                                                     glu ? N / 2 : 0);
   return hipGetLastError();
 }
 

@@ -76,7 +76,8 @@ struct AttnArgs {
   int chunk_tiles;  // tiles of 32 keys per workgroup chunk
   int n_chunks;     // grid.x
 };
-int attn_chunk_tiles(int len_upper, int n_q);
+int attn_chunk_tiles(int groups, int keys_upper);  // groups = B * Hkv * row tiles
+void attn_tune(int chunk_tiles);                   // tuning override, 0 = automatic
 size_t attn_workspace_bytes(int B, int Hkv, int hd, int G, int n_q, int len_upper);
 hipError_t launch_attention_bf16(const AttnArgs &a, hipStream_t s);
 // merges the split-KV partials (only needed when a.n_chunks > 1)
@@ -88,6 +89,7 @@ struct GemmArgs {
   void *y;
   int M, N, K;
   int out_f32;
+  int glu;          // bf16 only: w packed with glu=1, y = silu(gate) * up as elem [M][N/2]
   void *ws;         // split-K tickets (first GEMM_TICKET_BYTES, zero between launches) + partial tiles
   size_t ws_bytes;  // 0: no split-K
 };
@@ -97,7 +99,7 @@ size_t gemm_workspace_bytes(int M_max);
 void gemm_tune(int tile, int split_k);  // tuning overrides, 0 = automatic
 // bf16 weights are consumed in MFMA-operand-packed form (see gemm.hip); fp32 weights stay row-major
 size_t packed_weight_bytes(int N, int K, int dtype);
-hipError_t launch_pack_weight(const void *w, void *packed, int N, int K, int dtype, hipStream_t s);
+hipError_t launch_pack_weight(const void *w, void *packed, int N, int K, int glu, int dtype, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmArgs &a, hipStream_t s);
 hipError_t launch_gemm_f32(const GemmArgs &a, hipStream_t s);
 

@@ -77,21 +77,21 @@ class Engine:
         self._keep.append(t)
         return t
 
-    def sf_pack_weight(self, w):
+    def sf_pack_weight(self, w, glu=False):
         """row-major device tensor [N,K] -> packed device buffer (kept alive by the engine)."""
         N, K = w.shape
         nb = self.lib.sf_packed_weight_bytes(self.ctx, N, K)
         es = 2 if self.dtype_id == sfb.SF_BF16 else 4
         out = torch.empty(nb // es, dtype=self.tdtype, device=self.dev)
-        sfb.check(self.lib.sf_pack_weight(self.ctx, _ptr(w), _ptr(out), N, K, _stream()), "sf_pack_weight")
+        sfb.check(self.lib.sf_pack_weight(self.ctx, _ptr(w), _ptr(out), N, K, int(glu), _stream()), "sf_pack_weight")
         self._keep.append(out)
         return out
 
-    def _lin(self, a):
+    def _lin(self, a, glu=False):
         """upload + pack one linear weight; the row-major copy is dropped."""
         t = self._up(a)
         self._keep.pop()
-        p = self.sf_pack_weight(t)
+        p = self.sf_pack_weight(t, glu)
         torch.cuda.current_stream().synchronize()
         return p
 
@@ -103,11 +103,11 @@ class Engine:
 
         def gate_up(w, l=None):
             if "w_gate_up" in w:
-                return self._lin(w["w_gate_up"] if l is None else w["w_gate_up"][l])
+                return self._lin(w["w_gate_up"] if l is None else w["w_gate_up"][l], glu=True)
             g, u = (w["w_gate"], w["w_up"]) if l is None else (w["w_gate"][l], w["w_up"][l])
             g, u = (torch.as_tensor(np.asarray(g)) if not isinstance(g, torch.Tensor) else g,
                     torch.as_tensor(np.asarray(u)) if not isinstance(u, torch.Tensor) else u)
-            return self._lin(torch.cat([g, u], 0))
+            return self._lin(torch.cat([g, u], 0), glu=True)
         T = sfb.TargetWeights()
         self.w = {}
         for n in ("embed", "lm_head", "final_norm"):
@@ -245,6 +245,24 @@ class Engine:
         sfb.check(self.lib.sf_op_linear(self.ctx, _ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(y), M, N, K,
                                         int(out_f32), wsp, nb, _stream()), "sf_op_linear", self.ctx)
         return y
+
+    def sf_op_linear_swiglu(self, x, w_gate_up):
+        """x [M,K]; w_gate_up row-major [2F,K] device tensor (packed here) -> act [M,F]."""
+        M, K = x.shape
+        F = w_gate_up.shape[0] // 2
+        pk = self.sf_pack_weight(w_gate_up, glu=True)
+        self._keep.pop()
+        act = torch.empty(M, F, dtype=self.tdtype, device=self.dev)
+        if self.dtype_id == sfb.SF_BF16:
+            wsp, nb = self.linear_workspace(M)
+        else:
+            nb = M * 2 * F * 4 + 256
+            self._gu_ws = torch.empty(nb + 256, dtype=torch.uint8, device=self.dev)
+            wsp = C.c_void_p(self._gu_ws.data_ptr() + (-self._gu_ws.data_ptr()) % 256)
+        sfb.check(self.lib.sf_op_linear_swiglu(self.ctx, _ptr(x), _ptr(pk), _ptr(act), M, F, K, wsp, nb, _stream()),
+                  "sf_op_linear_swiglu", self.ctx)
+        self._pk_keep = pk
+        return act
 
     def sf_op_rmsnorm(self, x, gain, n_gain=1):
         M, d = x.shape

@@ -155,6 +155,20 @@ def test_rope_kv_append_and_layout_roundtrip(dtype, tol, hd):
     np.testing.assert_array_equal(kg.transpose(0, 2, 1, 3)[untouched], kc.transpose(0, 2, 1, 3)[untouched])
 
 
+@pytest.mark.parametrize("dtype,tol,M,F,K", [("bf16", BF16_TOL, 320, 1024, 512), ("bf16", BF16_TOL, 77, 96, 200),
+                                             ("bf16", BF16_TOL, 160, 2048, 4096), ("f32", 1e-4, 20, 1024, 256)])
+def test_linear_swiglu(dtype, tol, M, F, K):
+    g = synth.rng(12, M + F)
+    x = g.standard_normal((M, K), dtype=np.float32)
+    w = g.standard_normal((2 * F, K), dtype=np.float32) * (2.0 / np.sqrt(K))
+    if dtype == "bf16":
+        x, w = synth.to_bf16_values(x), synth.to_bf16_values(w)
+    eng = engine_only(shape_for(dtype, 2, 2, 64), 1, 64, 1)
+    act = eng.sf_op_linear_swiglu(dev(x, dtype), dev(w, dtype))
+    ref = sfo.silu_mul(sfo.linear(x, w[:F]), sfo.linear(x, w[F:]))
+    assert rel_err(to_np(act), ref) < tol
+
+
 @pytest.mark.parametrize("dtype,tol", [("bf16", BF16_TOL), ("f32", 1e-5)])
 def test_silu_mul(dtype, tol):
     g = synth.rng(9, 1)
