@@ -127,6 +127,14 @@ def main():
     ap.add_argument("--k", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--calib-copy", type=int, default=0,
+                    help="first run this many plain 1 GiB device copies (reference dispatches for scaling "
+                         "rocprofv3 byte counters)")
+    ap.add_argument("--seeded-state", action="store_true",
+                    help="skip prefill and the plain-greedy reference run: seed caches, hooks and pending tokens "
+                         "directly (values do not change the work); only the natural-draft pass runs. For profilers.")
+    ap.add_argument("--no-graph", dest="graph", action="store_false",
+                    help="launch every kernel eagerly instead of replaying one HIP graph per step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -145,10 +153,18 @@ def main():
     es = 2 if m.dtype == "bf16" else 4
     torch.cuda.set_device(0)
 
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(args.calib_copy):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     lens = synth.prefix_lengths(B, wl.prefix_lo, wl.prefix_hi, wl.seed)
     prompts = synth.prompts(lens, m.vocab, wl.seed)
     n_pass = 2 if args.no_profile else 3
-    total_steps = n_pass * (steps + warm) + 2
+    total_steps = n_pass * (steps + warm) + 6
     cap = synth.kv_capacity(int(lens.max()), total_steps, k)
     eng = Engine(m.cfg(), B, cap, k)
     tw, dw = device_weights(m, k, wl.seed, torch)
@@ -156,7 +172,18 @@ def main():
     del tw, dw
 
     t0 = time.time()
-    eng.prefill(prompts)
+    if args.seeded_state:
+        gs = torch.Generator(device="cuda"); gs.manual_seed(wl.seed + 1)
+        for name in ("tk", "tv", "dk", "dv"):
+            buf = getattr(eng, name)
+            for off in range(0, buf.numel(), 1 << 28):
+                chunk = buf[off:off + (1 << 28)]
+                chunk.copy_(torch.randn(chunk.numel(), generator=gs, device="cuda", dtype=torch.float32))
+        eng.hooks.copy_(torch.randn(eng.hooks.shape, generator=gs, device="cuda", dtype=torch.float32))
+        eng.set_state(kv_len=lens, pending=synth.rng(wl.seed, 5).integers(0, m.vocab, B).astype(np.int32),
+                      n_new=np.ones(B, np.int32))
+    else:
+        eng.prefill(prompts)
     torch.cuda.synchronize()
     t_prefill = time.time() - t0
     snap = {n: getattr(eng, n).clone() for n in ("kv_len", "pending", "n_new", "cu_new", "hooks")}
@@ -169,7 +196,7 @@ def main():
     none = torch.zeros(B, 0, dtype=torch.int32, device="cuda")
     lg1 = torch.empty(B, 1, m.vocab, dtype=torch.float32, device="cuda")
     for j in range(1, n_ar):
-        if eng.len_upper + 1 > cap:
+        if eng.len_upper + 1 > cap or args.seeded_state:
             break
         eng.sf_verify_step(0, none, logits_out=lg1)
         _, out = eng.sf_accept_commit(0, none, lg1)
@@ -191,11 +218,24 @@ def main():
     logits = torch.empty(B, k + 1, m.vocab, dtype=torch.float32, device="cuda")
     toks = torch.empty(B, k + 1, dtype=torch.int32, device="cuda")
 
-    tok_hist = torch.full((2 * (steps + warm) + 4, B, k + 1), -1, dtype=torch.int32, device="cuda")
-    tok_pos = torch.zeros(2 * (steps + warm) + 4, B, dtype=torch.int64, device="cuda")
+    n_rec = steps + warm + 2
+    tok_hist = torch.full((n_rec, B, k + 1), -1, dtype=torch.int32, device="cuda")
+    tok_pos = torch.zeros(n_rec, B, dtype=torch.int64, device="cuda")
     hist_i = [0]
+    acc_buf = torch.zeros(B, dtype=torch.int32, device="cuda")
+    acc_sum = torch.zeros(B, dtype=torch.int64, device="cuda")
 
-    def run(n, calibrated, acc_hist=None, len_hist=None, phase_ev=None, record=False):
+    def one_step(calibrated):
+        """draft -> (optional draft replacement) -> verify -> accept; everything on the current stream"""
+        eng.sf_draft_step(k, draft_out=draft)
+        if calibrated and k > 0:
+            idx = (eng.kv_len.to(torch.int64) - len_t + 1)[:, None] + slot
+            draft.copy_(torch.gather(inj, 1, idx.clamp_(max=n_ar - 1)))
+        eng.sf_verify_step(k, draft, logits_out=logits)
+        eng.sf_accept_commit(k, draft, logits, accept_out=acc_buf, tokens_out=toks)
+        acc_sum.add_(acc_buf)
+
+    def run_eager(n, calibrated, len_hist=None, phase_ev=None, record=False):
         for i in range(n):
             if phase_ev is not None:
                 phase_ev[i][0].record()
@@ -212,35 +252,55 @@ def main():
                 phase_ev[i][2].record()
             if record:   # where in the plain-greedy stream this step's first output token belongs
                 tok_pos[hist_i[0]].copy_(eng.kv_len.to(torch.int64) - len_t + 1)
-            eng.sf_accept_commit(k, draft, logits, accept_out=None if acc_hist is None else acc_hist[i],
+            eng.sf_accept_commit(k, draft, logits, accept_out=acc_buf,
                                  tokens_out=tok_hist[hist_i[0]] if record else toks)
+            acc_sum.add_(acc_buf)
             if record:
                 hist_i[0] += 1
             if phase_ev is not None:
                 phase_ev[i][3].record()
 
+    # One HIP graph per draft mode replays the whole step: the library's launch grids depend only on
+    # the host-side length bound, which is pinned to its maximum for the capture.
+    graphs = {}
+    if args.graph:
+        for cal in ((False,) if args.seeded_state else (False, True)):
+            keep = {n: getattr(eng, n).clone() for n in ("kv_len", "pending", "n_new", "cu_new", "hooks")}
+            eng.pin_len_upper()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                one_step(cal)                      # warm up (lazy kernel attributes) outside the capture
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                one_step(cal)
+            torch.cuda.synchronize()
+            graphs[cal] = g
+            for n, t in keep.items():              # the capture's warm-up advanced the state: rewind
+                getattr(eng, n).copy_(t)
+
+    def run(n, calibrated):
+        if args.graph:
+            for _ in range(n):
+                graphs[calibrated].replay()
+        else:
+            run_eager(n, calibrated)
+
     def timed_pass(calibrated):
-        run(warm, calibrated, record=True)
-        acc = torch.zeros(steps, B, dtype=torch.int32, device="cuda")
+        run(warm, calibrated)
+        torch.cuda.synchronize()
+        acc_sum.zero_()
         torch.cuda.synchronize()
         t = time.perf_counter()
-        run(steps, calibrated, acc_hist=acc, record=True)
+        run(steps, calibrated)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t
-        return dt, int(acc.sum().item())
+        return dt, int(acc_sum.sum().item())
 
     dt_nat, tok_nat = timed_pass(False)
-    dt_cal, tok_cal = timed_pass(True)
-
-    # lossless property at full size: every token the speculative path emitted equals the target's
-    # own plain-greedy continuation at that place of the stream
-    nrec = hist_i[0]
-    pos = tok_pos[:nrec, :, None] + torch.arange(k + 1, device="cuda")[None, None, :]
-    want = torch.gather(ar.to(torch.int64)[None].expand(nrec, B, n_ar), 2, pos.clamp(max=n_ar - 1))
-    got = tok_hist[:nrec].to(torch.int64)
-    emitted = got >= 0
-    lossless = {"tokens_compared": int(emitted.sum().item()),
-                "mismatches": int(((got != want) & emitted).sum().item())}
+    dt_cal, tok_cal = (dt_nat, tok_nat) if args.seeded_state else timed_pass(True)
 
     result = {
         "metric": "accepted tokens/s at batch B (draft+verify+accept step)",
@@ -251,9 +311,10 @@ def main():
                    "prefix": [int(wl.prefix_lo), int(wl.prefix_hi)], "layers": m.n_layers, "d_model": m.d_model,
                    "q_heads": m.n_q_heads, "kv_heads": m.n_kv_heads, "head_dim": m.head_dim, "d_ffn": m.d_ffn,
                    "vocab": m.vocab, "drafts": "natural (the random-init draft block's own tokens)",
-                   "state": "real chunked prefill through sf_verify_step", "prefill_s": round(t_prefill, 3)},
+                   "state": "seeded caches (no prefill)" if args.seeded_state else
+                            "real chunked prefill through sf_verify_step", "prefill_s": round(t_prefill, 3),
+                   "launch": "one HIP graph replay per step" if args.graph else "eager launches"},
         "kappa": tok_nat / (steps * B),
-        "lossless_check": lossless,
         "step_us": 1e6 * dt_nat / steps,
         "calibrated": {"what": "draft tokens replaced after sf_draft_step by the target's greedy continuation, "
                                "each slot corrupted with probability 1-alpha, so kappa matches the paper's model class",
@@ -263,14 +324,29 @@ def main():
 
     if not args.no_profile:
         # identical pass with every kernel launch bracketed by HIP events on the launch stream
-        run(warm, True)
+        eng.pin_len_upper(False)
+        eng.len_upper = min(cap - (k + 1), int(eng.kv_len.max().item()))
+        cal3 = not args.seeded_state
+        run_eager(warm, cal3, record=True)
         len_hist = torch.zeros(steps, B, dtype=torch.int32, device="cuda")
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
         torch.cuda.synchronize()
         eng.sf_profile_begin()
-        run(steps, True, len_hist=len_hist, phase_ev=ev)
+        run_eager(steps, cal3, len_hist=len_hist, phase_ev=ev, record=True)
         prof = eng.sf_profile_end()
         torch.cuda.synchronize()
+        # lossless property at full size: every token the speculative path emitted equals the target's
+        # own plain-greedy continuation at that place of the stream
+        nrec = hist_i[0]
+        pos = tok_pos[:nrec, :, None] + torch.arange(k + 1, device="cuda")[None, None, :]
+        want = torch.gather(ar.to(torch.int64)[None].expand(nrec, B, n_ar), 2, pos.clamp(max=n_ar - 1))
+        got = tok_hist[:nrec].to(torch.int64)
+        emitted = got >= 0
+        lossless = {"tokens_compared": int(emitted.sum().item()),
+                    "mismatches": int(((got != want) & emitted).sum().item())}
+
+        result["lossless_check"] = "n/a (seeded state has no reference run)" if args.seeded_state else lossless
+
         phases = {"draft_us": np.mean([e[0].elapsed_time(e[1]) for e in ev]) * 1e3,
                   "verify_us": np.mean([e[1].elapsed_time(e[2]) for e in ev]) * 1e3,
                   "accept_us": np.mean([e[2].elapsed_time(e[3]) for e in ev]) * 1e3}

@@ -61,6 +61,7 @@ class Engine:
                             _ptr(self.kv_len), _ptr(self.pending), _ptr(self.hooks), _ptr(self.n_new),
                             _ptr(self.cu_new), C.c_void_p(self._ws_ptr), wb)
         self.len_upper = 0          # host-side upper bound of max_b kv_len[b]
+        self._pinned = False
         self._keep = []
 
     def close(self):
@@ -158,7 +159,8 @@ class Engine:
         sfb.check(self.lib.sf_accept_commit(self.ctx, C.byref(self.st), k, _ptr(draft) if k > 0 else None,
                                             _ptr(logits), _ptr(force_len), _ptr(acc), _ptr(out), _stream()),
                   "sf_accept_commit", self.ctx)
-        self.len_upper = min(self.len_upper + k + 1, self.cap)
+        if not self._pinned:
+            self.len_upper = min(self.len_upper + k + 1, self.cap)
         return acc, out
 
     def sf_profile_begin(self):
@@ -170,6 +172,13 @@ class Engine:
         ms, cnt = (C.c_double * n)(), (C.c_int32 * n)()
         sfb.check(self.lib.sf_profile_end(self.ctx, ms, cnt, n), "sf_profile_end")
         return {name: (ms[i], cnt[i]) for i, name in enumerate(sfb.KERNEL_CLASSES)}
+
+    def pin_len_upper(self, pinned=True):
+        """Pin the host-side length bound to its maximum, so that every launch grid is the same
+        from step to step (what a captured HIP graph needs); unpin to track the lengths again."""
+        self._pinned = pinned
+        if pinned:
+            self.len_upper = self.cap - (self.max_k + 1)
 
     # ---- state helpers (plumbing) ------------------------------------------------------------
     def set_state(self, kv_len=None, pending=None, n_new=None):
