@@ -156,8 +156,9 @@ def main():
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
+        from paper_2511_20340_amd import binding as _b
         for _ in range(args.calib_copy):
-            dst.copy_(src)
+            _b.check(_b.lib().sf_calib_copy(dst.data_ptr(), src.data_ptr(), src.numel(), None), "sf_calib_copy")
         torch.cuda.synchronize()
         del src, dst
 

@@ -246,6 +246,10 @@ sf_status sf_op_argmax(const sf_ctx *ctx, const float *logits, int32_t M, int32_
  * split-KV combine, 3 RMSNorm, 4 rotary + K/V append, 5 SwiGLU gate, 6 embedding / hook copies,
  * 7 arg-max pass over the logits, 8 arg-max finish / accept-commit. */
 #define SF_N_KERNEL_CLASSES 9
+/* Measurement aid: a plain device-to-device copy kernel (`calib_copy_kernel`) of `bytes` (multiple of 16,
+ * 16-byte aligned pointers) that reads and writes every byte exactly once: the dispatch of known size
+ * against which hardware byte counters (FETCH_SIZE, WRITE_SIZE) are scaled. */
+sf_status sf_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
 sf_status sf_profile_begin(sf_ctx *ctx);
 sf_status sf_profile_end(sf_ctx *ctx, double *ms, int32_t *launches, int32_t n_class);
 

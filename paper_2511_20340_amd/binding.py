@@ -15,7 +15,7 @@ EXPORTS = [
     "sf_create", "sf_destroy", "sf_workspace_bytes", "sf_kv_cache_bytes", "sf_bind", "sf_draft_step",
     "sf_verify_step", "sf_accept_commit", "sf_kv_import", "sf_kv_export", "sf_attention_workspace_bytes",
     "sf_op_attention", "sf_packed_weight_bytes", "sf_pack_weight", "sf_linear_workspace_bytes", "sf_op_linear", "sf_op_linear_swiglu", "sf_tune_linear", "sf_tune_attention", "sf_op_rmsnorm", "sf_op_rope_kv_append", "sf_op_silu_mul",
-    "sf_argmax_workspace_bytes", "sf_op_argmax", "sf_profile_begin", "sf_profile_end", "sf_strerror", "sf_last_hip_error", "sf_version",
+    "sf_argmax_workspace_bytes", "sf_op_argmax", "sf_calib_copy", "sf_profile_begin", "sf_profile_end", "sf_strerror", "sf_last_hip_error", "sf_version",
 ]
 
 vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
@@ -96,6 +96,7 @@ def lib():
     L.sf_argmax_workspace_bytes.argtypes = [i32]
     L.sf_argmax_workspace_bytes.restype = sz
     L.sf_op_argmax.argtypes = [vp, vp, i32, i32, vp, vp, sz, vp]
+    L.sf_calib_copy.argtypes = [vp, vp, sz, vp]
     L.sf_profile_begin.argtypes = [vp]
     L.sf_profile_end.argtypes = [vp, P(C.c_double), P(i32), i32]
     L.sf_strerror.argtypes = [i32]

@@ -531,6 +531,11 @@ sf_status sf_op_argmax(const sf_ctx *c, const float *logits, int32_t M, int32_t 
   return r.st;
 }
 
+sf_status sf_calib_copy(void *dst, const void *src, size_t bytes, void *stream) {
+  if (!dst || !src || bytes % 16 || (((uintptr_t)dst | (uintptr_t)src) % 16)) return SF_EINVAL;
+  return launch_calib_copy(src, dst, bytes, (hipStream_t)stream) == hipSuccess ? SF_OK : SF_EHIP;
+}
+
 sf_status sf_profile_begin(sf_ctx *c) {
   if (!c) return SF_EINVAL;
   c->prof.on = true;

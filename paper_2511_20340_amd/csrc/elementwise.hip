@@ -227,6 +227,12 @@ __global__ void kv_convert_kernel(const T *__restrict__ src, T *__restrict__ dst
   else dst[idx] = src[t_idx];
 }
 
+// plain streaming copy of 16-byte units: the reference dispatch for scaling profiler byte counters
+__global__ __launch_bounds__(256) void calib_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
+                                                         size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
 template <typename T>
 hipError_t rmsnorm_t(const NormArgs &a, hipStream_t s) {
   rmsnorm_kernel<T><<<a.M, 256, 0, s>>>((const T *)a.x, (const T *)a.gain, (T *)a.y, a.d, a.n_gain, a.eps, a.map,
@@ -243,6 +249,11 @@ hipError_t rope_kv_t(const RopeArgs &a, hipStream_t s) {
 }
 
 }  // namespace
+
+hipError_t launch_calib_copy(const void *src, void *dst, size_t bytes, hipStream_t s) {
+  calib_copy_kernel<<<8192, 256, 0, s>>>((const uint4 *)src, (uint4 *)dst, bytes / 16);
+  return hipGetLastError();
+}
 
 hipError_t launch_rmsnorm(const NormArgs &a, int dtype, hipStream_t s) {
   return dtype == SF_BF16 ? rmsnorm_t<bf16_t>(a, s) : rmsnorm_t<float>(a, s);

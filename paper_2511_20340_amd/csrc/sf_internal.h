@@ -116,6 +116,7 @@ struct NormArgs {
   const int32_t *n_new;
 };
 hipError_t launch_rmsnorm(const NormArgs &a, int dtype, hipStream_t s);
+hipError_t launch_calib_copy(const void *src, void *dst, size_t bytes, hipStream_t s);
 
 struct RopeArgs {
   const void *qkv;  // [M][(Hq+2Hkv)*hd] or, kv_only, [M][2*Hkv*hd]
