@@ -361,13 +361,16 @@ hipError_t launch_pack_weight(const void *w, void *packed, int N, int K, int glu
 hipError_t launch_gemm_bf16(const GemmArgs &a, hipStream_t s) {
   int tile = g_tile;
   if (tile == 0) {
-    // rows per workgroup: 160 when M is a multiple of it (M = 160, 320, 640, 1280: B*(k+1) with
-    // k = 4), otherwise 128 / 64 / 32 by size
-    if (a.M <= 32) tile = 1;
-    else if (a.M <= 64) tile = 2;
+    // Rows per workgroup.  Small weight matrices stay resident in L2 / the last-level cache, so
+    // re-reading them for every 32- or 64-row M-tile is cheap and the many small workgroups hide
+    // the per-slice latency better; large ones are streamed once per 160 (or 128) rows.
+    const size_t wbytes = (size_t)a.N * a.K * 2;
+    const size_t MB = 1u << 20;
+    if (a.M <= 32 || wbytes <= 40 * MB) tile = 1;
+    else if (a.M <= 64 || wbytes <= 64 * MB || (a.M <= 160 && wbytes <= 160 * MB)) tile = 2;
     else if (a.M <= 128) tile = 3;
     else if (a.M <= 160 || a.M % 160 == 0) tile = 5;
-    else if (a.M % 128 == 0 && a.M <= 512) tile = 4;
+    else if (a.M % 128 == 0 && a.M <= 512 && a.N >= 65536) tile = 4;
     else tile = 3;
   }
   switch (tile) {
