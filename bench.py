@@ -300,6 +300,45 @@ def main():
         dt = time.perf_counter() - t
         return dt, int(acc_sum.sum().item())
 
+    # plain autoregressive decoding of the same target through the same engine (k = 0: one token per
+    # sequence per target call), the "W/o SD" row of the paper's tables: timed over the same number of
+    # target calls, then the state is rewound
+    ar_ms = None
+    if not args.seeded_state and k > 0:
+        keep = {n: getattr(eng, n).clone() for n in ("kv_len", "pending", "n_new", "cu_new", "hooks")}
+        pinned = eng._pinned
+        eng.pin_len_upper(False)
+        eng.len_upper = len0
+        acc1 = torch.empty(B, dtype=torch.int32, device="cuda")
+        out1 = torch.empty(B, 1, dtype=torch.int32, device="cuda")
+
+        def ar_step():
+            eng.sf_verify_step(0, none, logits_out=lg1)
+            eng.sf_accept_commit(0, none, lg1, accept_out=acc1, tokens_out=out1)
+        if args.graph:
+            eng.pin_len_upper()
+            ar_step()
+            torch.cuda.synchronize()
+            g0 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g0):
+                ar_step()
+            step0 = g0.replay
+        else:
+            step0 = ar_step
+        for _ in range(warm):
+            step0()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(steps):
+            step0()
+        torch.cuda.synchronize()
+        ar_ms = 1e3 * (time.perf_counter() - t) / steps
+        for n, t_ in keep.items():
+            getattr(eng, n).copy_(t_)
+        eng.pin_len_upper(pinned)
+        if not pinned:
+            eng.len_upper = len0
+
     dt_nat, tok_nat = timed_pass(False)
     dt_cal, tok_cal = (dt_nat, tok_nat) if args.seeded_state else timed_pass(True)
 
@@ -322,6 +361,16 @@ def main():
                        "kappa_target": kappa_t, "alpha": alpha, "kappa": tok_cal / (steps * B),
                        "value": tok_cal / dt_cal, "unit": "accepted tokens/s", "ms_per_step": 1e3 * dt_cal / steps},
     }
+
+    if ar_ms is not None:
+        # the paper's table format: TPS, speed-up over no-SD, kappa, theta = kappa / speed-up
+        ar_tps = B / (ar_ms * 1e-3)
+        result["vs_plain_decoding"] = {
+            "plain_tokens_per_s": ar_tps, "plain_ms_per_step": ar_ms,
+            "natural": {"speedup": result["value"] / ar_tps, "kappa": result["kappa"],
+                        "theta": result["kappa"] / (result["value"] / ar_tps)},
+            "calibrated": {"speedup": result["calibrated"]["value"] / ar_tps, "kappa": result["calibrated"]["kappa"],
+                           "theta": result["calibrated"]["kappa"] / (result["calibrated"]["value"] / ar_tps)}}
 
     if not args.no_profile:
         # identical pass with every kernel launch bracketed by HIP events on the launch stream

@@ -65,7 +65,7 @@ Arena plan(const sf_ctx *c, int B, int k, int cap) {
   a.qkv = take(M * (nq + 2 * nkv) * es);
   a.qr = take(M * nq * es);
   a.ao = take(M * nq * es);
-  a.gu = take(M * 2 * F * sizeof(float));
+  a.gu = take(m.dtype == SF_F32 ? M * 2 * F * sizeof(float) : 0);  // bf16 gates in the GEMM epilogue
   a.act = take(M * F * es);
   a.table = take(Mx * (m.head_dim / 2) * sizeof(float2));
   const int G = m.n_q_heads / m.n_kv_heads;
@@ -107,6 +107,7 @@ struct Run {
   sf_status st = SF_OK;
   void *gemm_ws = nullptr;
   size_t gemm_ws_bytes = 0;
+  int plan_rows = 0;  // rows the linear layers' K partition is chosen for (0: the launch's own M)
   // a stale error left by an earlier, unrelated HIP call of the process must not be blamed on us
   Run(const sf_ctx *ctx, hipStream_t stream) : c(ctx), s(stream) { (void)hipGetLastError(); }
   bool ok(hipError_t e) {
@@ -137,6 +138,7 @@ void gemm(Run &r, int dtype, const void *x, const void *w, const void *bias, con
           int K, int out_f32, int glu = 0) {
   if (r.st != SF_OK) return;
   GemmArgs g{x, w, bias, res, y, M, N, K, out_f32, glu, r.gemm_ws, r.gemm_ws_bytes};
+  g.plan_M = r.plan_rows;
   LAUNCH(K_GEMM, dtype == SF_BF16 ? launch_gemm_bf16(g, r.s) : launch_gemm_f32(g, r.s));
 }
 
@@ -278,6 +280,9 @@ sf_status sf_verify_step(sf_ctx *c, const sf_state *st, int32_t k, const int32_t
   const int nq = m.n_q_heads * m.head_dim, nkv = m.n_kv_heads * m.head_dim;
   Run r{c, (hipStream_t)stream};
   r.gemm_ws = ws + A.gemm_ws; r.gemm_ws_bytes = A.gemm_ws_bytes;
+  // the target's logits for a position must not depend on how many draft positions are verified
+  // with it: every k of this state uses the K partition chosen for the largest block
+  r.plan_rows = B * qm;
   LAUNCH(K_EMBED_HOOK, launch_embed(c->tw.embed, st->pending, draft, h, st->hooks, B, k, qm, d, m.vocab, m.dtype, r.s));
   RopeArgs ra{};
   ra.qkv = qkv; ra.q_out = qr; ra.kv_len = st->kv_len; ra.n_new = nullptr; ra.table = (float2 *)(ws + A.table);
@@ -450,7 +455,7 @@ sf_status sf_tune_attention(int32_t chunk_tiles) {
 }
 
 sf_status sf_tune_linear(int32_t tile, int32_t split_k) {
-  if (tile < 0 || tile > 7 || split_k < 0 || split_k > 64) return SF_EINVAL;
+  if (tile < 0 || tile > gemm_num_tiles() || split_k < 0 || split_k > 64) return SF_EINVAL;
   gemm_tune(tile, split_k);
   return SF_OK;
 }

@@ -4,11 +4,16 @@
 // matrices that are streamed from HBM exactly once.  The weights are therefore kept PACKED in
 // MFMA-operand order (pack_weight below): for every 32-row block of W and every 16-wide k-step
 // one 1 KiB unit holds, lane by lane, the 8 bf16 a lane feeds to v_mfma_f32_32x32x16_bf16.  A
-// wavefront owns TN such row blocks and streams them straight from global memory into operand
-// registers with fully coalesced 16-byte loads -- no LDS traffic, no barrier on the weight side.
-// Only the activations (BM = TM*32 rows x 64 k) are staged through LDS (register-prefetched
-// double buffer, rows padded to 72 elements: conflict-free 16-byte operand reads) and shared by
-// the 4 waves of the workgroup, which cover 4*TN*32 output columns.
+// wavefront owns one such row block per output tile and streams its units straight from global
+// memory into operand registers with fully coalesced 16-byte loads -- no LDS traffic, no barrier
+// on the weight side.  Only the activations (BM = TM*32 rows x 64 k) are staged through LDS
+// (double buffer, rows padded to 72 elements: conflict-free 16-byte operand reads) and shared by
+// the 4 or 8 waves of the workgroup, which cover 128 or 256 output columns.
+//
+// Memory pipeline: every wave keeps a ring of R K-slices in flight (weights in registers, the
+// activation chunks that go with them in registers until their turn to enter LDS).  All loads are
+// unconditional and issued in the order of use, so the compiler's vmcnt waits only ever cover the
+// slice that is needed next.
 //
 // Parallelism for small N*M: the K dimension is split over `split_k` workgroups per tile.  Each
 // leaves its fp32 partial tile in the workspace and takes a ticket; the last one to arrive adds
@@ -21,6 +26,8 @@
 // fp32 path: plain SIMT tiling on row-major weights for the small fp32 configuration.
 #include "sf_internal.h"
 
+#include <algorithm>
+
 namespace sf {
 namespace {
 
@@ -28,113 +35,23 @@ constexpr int BK = 64;
 constexpr int LDK = 72;  // padded LDS row length in bf16 elements (144 B)
 constexpr int XCDS = 8;
 
-template <int TM, int TN, int OCC>
-__global__ __launch_bounds__(256, OCC) void gemm_wd_kernel(const bf16_t *__restrict__ A, const uint4 *__restrict__ Wp,
-                                                      const bf16_t *__restrict__ bias, const bf16_t *residual,
-                                                      void *Y, int M, int N, int K, int out_f32, int tiles_m,
-                                                      int tiles_n, int split_k, int kt_per_split,
-                                                      float *__restrict__ partial, unsigned *__restrict__ tickets,
-                                                      int glu) {
-  constexpr int BM = TM * 32;
-  extern __shared__ __attribute__((aligned(16))) bf16_t sA[];  // [2][BM][LDK]
-  __shared__ unsigned s_ticket;
-
-  // XCD-aware tile assignment: consecutive workgroup ids round-robin over the 8 XCDs; inside an
-  // XCD the M-tiles of a column block are adjacent, then the K splits, then the next column block.
-  const int id = blockIdx.x;
-  const int xcd = id % XCDS, j = id / XCDS;
-  const int tm = j % tiles_m, ks = (j / tiles_m) % split_k;
-  const int tn = (j / (tiles_m * split_k)) * XCDS + xcd;
-  if (tn >= tiles_n) return;
-  const int m0 = tm * BM;
-
+// What every bf16 kernel variant does once a workgroup holds its accumulators: the split-K hand-over
+// (partials, ticket, ordered sum in the last workgroup to arrive) and the output epilogue.
+template <int TM, int TN, int NW = 4>
+__device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const bf16_t *__restrict__ bias,
+                                            const bf16_t *residual, void *Y, int M, int N, int out_f32, int tiles_m,
+                                            int split_k, float *__restrict__ partial,
+                                            unsigned *__restrict__ tickets, int glu, int tm, int tn, int ks, int m0,
+                                            int nb0, unsigned &s_ticket) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
-  const int n_blocks = (N + 31) >> 5;        // 32-row blocks of W
-  const int k_steps = (K + 15) >> 4;         // 16-wide k-steps (packed K is padded to 16)
-  const int nb0 = (tn * 4 + wave) * TN;      // this wave's first W row block
-
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int a = 0; a < TM; ++a)
-#pragma unroll
-    for (int b = 0; b < TN; ++b)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-
-  uint4 ra[TM];                    // activation chunks in flight to LDS
-  uint4 wcur[4][TN], wnxt[4][TN];  // weight operands of the current / next K slice
-  auto aload = [&](int k0) {
-#pragma unroll
-    for (int c = 0; c < TM; ++c) {
-      const int cid = tid + 256 * c, row = cid >> 3, kc = (cid & 7) * 8;
-      const int gr = m0 + row;
-      ra[c] = (gr < M && k0 + kc < K) ? *reinterpret_cast<const uint4 *>(A + (size_t)gr * K + k0 + kc)
-                                      : make_uint4(0, 0, 0, 0);
-    }
-  };
-  auto astore = [&](int buf) {
-#pragma unroll
-    for (int c = 0; c < TM; ++c) {
-      const int cid = tid + 256 * c, row = cid >> 3, kc = (cid & 7) * 8;
-      *reinterpret_cast<uint4 *>(sA + (buf * BM + row) * LDK + kc) = ra[c];
-    }
-  };
-  auto wload = [&](uint4 (&w)[4][TN], int kt) {
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-#pragma unroll
-      for (int b = 0; b < TN; ++b) {
-        const int kstep = kt * 4 + s, nb = nb0 + b;
-        w[s][b] = (kstep < k_steps && nb < n_blocks) ? Wp[((size_t)nb * k_steps + kstep) * 64 + lane]
-                                                     : make_uint4(0, 0, 0, 0);
-      }
-  };
-
-  const int KT = (K + BK - 1) / BK;
-  const int kt0 = ks * kt_per_split, kt1 = min(KT, kt0 + kt_per_split);
-  if (kt0 < kt1) {
-    wload(wcur, kt0);
-    aload(kt0 * BK);
-    astore(0);
-  }
-  __syncthreads();
-  for (int kt = kt0; kt < kt1; ++kt) {
-    const int buf = (kt - kt0) & 1;
-    const bool more = kt + 1 < kt1;
-    if (more) {
-      wload(wnxt, kt + 1);
-      aload((kt + 1) * BK);
-    }
-    const bf16_t *pa = sA + (buf * BM + ln) * LDK + lh * 8;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-#pragma unroll
-      for (int a = 0; a < TM; ++a) {
-        const bf16x8 fa = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pa + a * 32 * LDK + s * 16));
-#pragma unroll
-        for (int b = 0; b < TN; ++b)
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, __builtin_bit_cast(bf16x8, wcur[s][b]), acc[a][b],
-                                                              0, 0, 0);
-      }
-    }
-    if (more) {
-      astore(buf ^ 1);
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int b = 0; b < TN; ++b) wcur[s][b] = wnxt[s][b];
-    }
-    __syncthreads();
-  }
-
   if (split_k > 1) {
     // Partial tiles in register order: [tile][split][wave][TM][TN][reg][lane].  They are written
     // and read with agent-scope accesses (write-through / cache-bypassing), so no L2-wide
     // writeback or invalidate is needed to make them visible to the workgroup that finishes.
     const size_t tile = (size_t)tn * tiles_m + tm;
     constexpr size_t PER_WAVE = (size_t)TM * TN * 64 * 16;
-    float *mine = partial + ((tile * split_k + ks) * 4 + wave) * PER_WAVE;
+    float *mine = partial + ((tile * split_k + ks) * NW + wave) * PER_WAVE;
 #pragma unroll
     for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -155,7 +72,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_wd_kernel(const bf16_t *__restr
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
     for (int s = 0; s < split_k; ++s) {  // fixed order: the sum does not depend on arrival order
-      const float *p = partial + ((tile * split_k + s) * 4 + wave) * PER_WAVE;
+      const float *p = partial + ((tile * split_k + s) * NW + wave) * PER_WAVE;
 #pragma unroll
       for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -192,7 +109,9 @@ __global__ __launch_bounds__(256, OCC) void gemm_wd_kernel(const bf16_t *__restr
     return;
   }
 
-  // epilogue: lane holds column ln, rows c_row(v, lh) of every 32x32 tile
+  // epilogue: lane holds column ln, rows c_row(v, lh) of every 32x32 tile.  y may be the residual
+  // buffer itself, so the block's residual values are all fetched before its first store (one wait
+  // per block instead of one per element).
 #pragma unroll
   for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -200,17 +119,137 @@ __global__ __launch_bounds__(256, OCC) void gemm_wd_kernel(const bf16_t *__restr
       const int col = (nb0 + b) * 32 + ln;
       if (col >= N) continue;
       const float bv = bias ? bf2f(bias[col]) : 0.f;
+      bf16_t res[16];
+      if (residual) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = min(m0 + a * 32 + c_row(v, lh), M - 1);
+          res[v] = residual[(size_t)row * N + col];
+        }
+      }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = m0 + a * 32 + c_row(v, lh);
         if (row >= M) continue;
         float r = acc[a][b][v] + bv;
         const size_t o = (size_t)row * N + col;
-        if (residual) r += bf2f(residual[o]);
+        if (residual) r += bf2f(res[v]);
         if (out_f32) reinterpret_cast<float *>(Y)[o] = r;
         else reinterpret_cast<bf16_t *>(Y)[o] = f2bf(r);
       }
     }
+}
+
+// The bf16 kernel.  TM 32-row activation blocks x TN weight row blocks per wave, NW waves, ring
+// depth R.  Slot indices are compile-time after unrolling by R; the trip count is a multiple of R
+// (slices past the workgroup's K range contribute zeros).
+template <int TM, int TN, int R, int OCC, int NW>
+__global__ __launch_bounds__(64 * NW, OCC) void gemm_ring_kernel(const bf16_t *__restrict__ A,
+                                                        const uint4 *__restrict__ Wp,
+                                                        const bf16_t *__restrict__ bias, const bf16_t *residual,
+                                                        void *Y, int M, int N, int K, int out_f32, int tiles_m,
+                                                        int tiles_n, int split_k, int kt_per_split,
+                                                        float *__restrict__ partial,
+                                                        unsigned *__restrict__ tickets, int glu) {
+  static_assert(R >= 2, "the slot after the current one holds the next activation chunk");
+  constexpr int BM = TM * 32;
+  constexpr int NT = 64 * NW;              // threads
+  constexpr int CH = TM * 256;             // 16-byte activation chunks per K slice
+  constexpr int CPT = (CH + NT - 1) / NT;  // chunks per thread
+  extern __shared__ __attribute__((aligned(16))) bf16_t sA[];  // [2][BM][LDK]
+  __shared__ unsigned s_ticket;
+
+  const int id = blockIdx.x;
+  const int xcd = id % XCDS, j = id / XCDS;
+  const int tm = j % tiles_m, ks = (j / tiles_m) % split_k;
+  const int tn = (j / (tiles_m * split_k)) * XCDS + xcd;
+  if (tn >= tiles_n) return;
+  const int m0 = tm * BM;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ln = lane & 31, lh = lane >> 5;
+  const int n_blocks = (N + 31) >> 5;
+  const int k_steps = (K + 15) >> 4;
+  const int nb0 = (tn * NW + wave) * TN;
+  const int KT = (K + BK - 1) / BK;
+  const int kt0 = ks * kt_per_split, kt1 = min(KT, kt0 + kt_per_split);
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int a = 0; a < TM; ++a)
+#pragma unroll
+    for (int b = 0; b < TN; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  uint4 ra[R][CPT];
+  uint4 w[R][4][TN];
+  // Every load is unconditional (addresses clamped into the operands), so the compiler can count
+  // how many are in flight.  Rows >= M and columns >= N compute garbage that the epilogue never
+  // writes; K positions outside this workgroup's slice are zeroed on the activation side when the
+  // chunk goes to LDS, which silences whatever weight the clamped address fetched.
+  auto aload = [&](uint4 (&r)[CPT], int kt) {
+    const int ktc = min(kt, KT - 1);
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int cid = min(tid + NT * c, CH - 1), row = cid >> 3, kc = (cid & 7) * 8;
+      const int gr = min(m0 + row, M - 1), kk = min(ktc * BK + kc, K - 8);
+      r[c] = *reinterpret_cast<const uint4 *>(A + (size_t)gr * K + kk);
+    }
+  };
+  auto astore = [&](int buf, const uint4 (&r)[CPT], int kt) {
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int cid = tid + NT * c, row = cid >> 3, kc = (cid & 7) * 8;
+      if (CH % NT != 0 && cid >= CH) continue;
+      const bool live = kt < kt1 && kt * BK + kc < K;
+      uint4 v = r[c];
+      v.x = live ? v.x : 0u; v.y = live ? v.y : 0u; v.z = live ? v.z : 0u; v.w = live ? v.w : 0u;
+      *reinterpret_cast<uint4 *>(sA + (buf * BM + row) * LDK + kc) = v;
+    }
+  };
+  auto wload = [&](uint4 (&wr)[4][TN], int kt) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int b = 0; b < TN; ++b) {
+        const int kstep = min(kt * 4 + s, k_steps - 1), nb = min(nb0 + b, n_blocks - 1);
+        wr[s][b] = Wp[((size_t)nb * k_steps + kstep) * 64 + lane];
+      }
+  };
+
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    aload(ra[r], kt0 + r);
+    wload(w[r], kt0 + r);
+  }
+  astore(0, ra[0], kt0);
+  __syncthreads();
+  for (int base = kt0; base < kt1; base += R) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int kt = base + r, buf = (kt - kt0) & 1;
+      const bf16_t *pa = sA + (buf * BM + ln) * LDK + lh * 8;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+#pragma unroll
+        for (int a = 0; a < TM; ++a) {
+          const bf16x8 fa =
+              __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pa + a * 32 * LDK + s * 16));
+#pragma unroll
+          for (int b = 0; b < TN; ++b)
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, __builtin_bit_cast(bf16x8, w[r][s][b]),
+                                                                acc[a][b], 0, 0, 0);
+        }
+      }
+      astore(buf ^ 1, ra[(r + 1) % R], kt + 1);  // the chunk of slice kt + 1
+      aload(ra[r], kt + R);              // this slot's next tenant, activations first: needed first
+      wload(w[r], kt + R);
+      __syncthreads();
+    }
+  }
+  gemm_finish<TM, TN, NW>(acc, bias, residual, Y, M, N, out_f32, tiles_m, split_k, partial, tickets, glu, tm, tn, ks, m0, nb0,
+                      s_ticket);
 }
 
 // row-major [N][K] -> packed units; one thread per 16-byte operand register
@@ -243,55 +282,124 @@ struct Plan {
   size_t partial_bytes, ticket_bytes;
 };
 
-// The split factor depends on the weight shape only (never on M), so a row's result is
-// bit-identical whatever else is batched with it: ~256 workgroups per M-tile, at least 8 K slices
-// (512 of K) per split.  Shapes with enough column tiles are not split.
-int auto_split(int N, int K) {
-  const int KT = (K + BK - 1) / BK;
-  const int col_tiles = (N + 127) / 128;
-  int s = 1;
-  while (s * 2 * col_tiles <= 256 && KT / (s * 2) >= 8 && s < 16) s *= 2;
-  return s;
-}
-
-Plan make_plan(int M, int N, int K, int BM, int BN, int split_req) {
+// split_k workgroups share a tile's K range in whole ring rounds (R slices each)
+Plan make_plan(int M, int N, int K, int BM, int BN, int split, int gran) {
   Plan p;
   p.tiles_m = (M + BM - 1) / BM;
   p.tiles_n = (N + BN - 1) / BN;
   const int KT = (K + BK - 1) / BK;
   const int tiles = p.tiles_m * p.tiles_n;
-  int s = split_req > 0 ? split_req : (M <= 640 ? auto_split(N, K) : 1);
-  s = s < 1 ? 1 : (s > KT ? KT : s);
-  p.kt_per_split = (KT + s - 1) / s;
+  const int s = split < 1 ? 1 : (split > KT ? KT : split);
+  p.kt_per_split = ((KT + s - 1) / s + gran - 1) / gran * gran;
   p.split_k = (KT + p.kt_per_split - 1) / p.kt_per_split;
   p.partial_bytes = p.split_k > 1 ? (size_t)tiles * p.split_k * BM * BN * sizeof(float) : 0;
   p.ticket_bytes = p.split_k > 1 ? (size_t)tiles * sizeof(unsigned) : 0;
   return p;
 }
 
-template <int TM, int TN, int OCC>
-hipError_t run_wd(const GemmArgs &a, hipStream_t s, int split_req) {
-  constexpr int BM = TM * 32, BN = 4 * TN * 32;
-  Plan p = make_plan(a.M, a.N, a.K, BM, BN, split_req);
-  if (p.split_k > 1 && (!a.ws || a.ws_bytes < GEMM_TICKET_BYTES + p.partial_bytes ||
-                        p.ticket_bytes > GEMM_TICKET_BYTES)) {
-    p = make_plan(a.M, a.N, a.K, BM, BN, 1);  // no room for partials: single pass
-  }
+bool plan_fits(const Plan &p, const void *ws, size_t ws_bytes) {
+  return p.split_k == 1 ||
+         (ws && ws_bytes >= GEMM_TICKET_BYTES + p.partial_bytes && p.ticket_bytes <= GEMM_TICKET_BYTES);
+}
+
+// mode 0: launch; mode 1: only report whether (split) fits the workspace
+template <int TM, int TN, int R, int OCC, int NW>
+hipError_t run_ring(const GemmArgs &a, hipStream_t s, int split, int mode) {
+  constexpr int BM = TM * 32, BN = NW * TN * 32;
+  const Plan p = make_plan(a.M, a.N, a.K, BM, BN, split, R);
+  if (!plan_fits(p, a.ws, a.ws_bytes)) return hipErrorInvalidValue;
+  if (mode == 1) return hipSuccess;
   const int groups = (p.tiles_n + XCDS - 1) / XCDS;
   const size_t lds = (size_t)2 * BM * LDK * sizeof(bf16_t);
-  auto kern = gemm_wd_kernel<TM, TN, OCC>;
-  static bool attr_done = false;
-  if (!attr_done && lds > 48 * 1024) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)lds);
-    attr_done = true;
-  }
   unsigned *tickets = (unsigned *)a.ws;
   float *partial = a.ws ? (float *)((char *)a.ws + GEMM_TICKET_BYTES) : nullptr;
-  kern<<<dim3(groups * XCDS * p.tiles_m * p.split_k), dim3(256), lds, s>>>(
+  gemm_ring_kernel<TM, TN, R, OCC, NW><<<dim3(groups * XCDS * p.tiles_m * p.split_k), dim3(64 * NW), lds, s>>>(
       (const bf16_t *)a.x, (const uint4 *)a.w, (const bf16_t *)a.bias, (const bf16_t *)a.residual, a.y, a.M, a.N,
       a.K, a.out_f32, p.tiles_m, p.tiles_n, p.split_k, p.kt_per_split, partial, tickets, a.glu);
   return hipGetLastError();
+}
+
+// Tile configurations: rows per workgroup TM*32, columns NW*32 (one 32-column block per wave).
+//   id  TM  ring  wg/CU  waves
+hipError_t dispatch(int tile, const GemmArgs &a, hipStream_t s, int split, int mode) {
+  switch (tile) {
+    case 1: return run_ring<1, 1, 4, 4, 4>(a, s, split, mode);
+    case 2: return run_ring<2, 1, 4, 3, 4>(a, s, split, mode);
+    case 3: return run_ring<3, 1, 4, 2, 4>(a, s, split, mode);
+    case 4: return run_ring<4, 1, 3, 2, 4>(a, s, split, mode);
+    case 5: return run_ring<5, 1, 3, 2, 4>(a, s, split, mode);
+    case 6: return run_ring<2, 1, 4, 1, 8>(a, s, split, mode);
+    case 7: return run_ring<3, 1, 4, 1, 8>(a, s, split, mode);
+    case 8: return run_ring<4, 1, 3, 1, 8>(a, s, split, mode);
+    case 9: return run_ring<5, 1, 3, 1, 8>(a, s, split, mode);
+    case 10: return run_ring<5, 1, 2, 1, 8>(a, s, split, mode);
+    default: return hipErrorInvalidValue;
+  }
+}
+constexpr int N_TILES = 10;
+constexpr int TILE_TM[N_TILES + 1] = {0, 1, 2, 3, 4, 5, 2, 3, 4, 5, 5};
+
+// Heuristic choice (used when nothing was measured for the shape).  What the sweeps on MI355X
+// showed: a compute unit draws at most ~20-40 B/clk from L2, so both the weight re-reads of the
+// M-tiles and the activation re-reads of the column tiles count; ~224 workgroups fill the chip;
+// splitting K costs a partial-tile round trip and a serial tail, so it is used only when the
+// unsplit grid is too small and K is long.
+constexpr int WG_FULL = 224, WG_SPLIT = 192;
+constexpr size_t REREAD_CAP = 384u << 20;
+
+int pow2floor(int v) { int p = 1; while (p * 2 <= v) p *= 2; return p; }
+
+GemmConfig pick(int M, int N, int K, size_t ws_bytes, int fixed_split) {
+  const int KT = (K + BK - 1) / BK;
+  const size_t wbytes = (size_t)N * K * 2;
+  const int max_tm = std::min(5, (M + 31) / 32);
+  const int cols4 = (N + 127) / 128, cols8 = (N + 255) / 256;
+  auto reread_ok = [&](int tm) {
+    const int tiles_m = (M + tm * 32 - 1) / (tm * 32);
+    return tm == max_tm || (size_t)tiles_m * wbytes <= REREAD_CAP;
+  };
+  auto with_waves = [&](int tm, int split) {  // 8-wave workgroups when the grid stays full
+    const int tiles_m = (M + tm * 32 - 1) / (tm * 32);
+    return (tm >= 2 && split == 1 && tiles_m * cols8 >= WG_FULL) ? tm + 4 : tm;
+  };
+  auto fits = [&](int tm, int split) {
+    if (split == 1) return true;
+    const Plan p = make_plan(M, N, K, tm * 32, 128, split, 4);
+    return ws_bytes >= GEMM_TICKET_BYTES + p.partial_bytes && p.ticket_bytes <= GEMM_TICKET_BYTES;
+  };
+  if (fixed_split <= 1) {
+    for (int tm = max_tm; tm >= 1; --tm) {
+      const int tiles_m = (M + tm * 32 - 1) / (tm * 32);
+      if (tiles_m * cols4 >= WG_FULL && reread_ok(tm)) return {with_waves(tm, 1), 1};
+    }
+    if (fixed_split == 1) {
+      for (int tm = 1; tm <= max_tm; ++tm)
+        if (reread_ok(tm)) return {tm, 1};
+      return {max_tm, 1};
+    }
+  }
+  // partial tiles cost 8 bytes per output element and split (written, then read): keep that
+  // below the weight bytes, and at least 8 K slices per workgroup
+  const int split_cap = std::max(1, std::min({16, pow2floor(std::max(1, K / (4 * std::max(M, 1)))), KT / 8}));
+  GemmConfig fallback = {1, 1};
+  for (int tm = max_tm; tm >= 1; --tm) {
+    const int tiles_m = (M + tm * 32 - 1) / (tm * 32);
+    const int wgs = tiles_m * cols4;
+    int sp = 1;
+    if (fixed_split > 1) {
+      sp = fixed_split;
+    } else {
+      while (wgs * sp < WG_FULL && sp * 2 <= split_cap) {
+        if (wgs * sp >= 128 && KT / sp <= 32) break;  // enough workgroups for a short K loop
+        sp *= 2;
+      }
+      while (sp > 1 && !fits(tm, sp)) sp /= 2;
+    }
+    if (!reread_ok(tm)) continue;
+    fallback = {tm, sp};
+    if (wgs * sp >= WG_SPLIT) return fallback;
+  }
+  return fallback;
 }
 
 // fp32: 64x64 tile, 16 wide k slices, each thread a 4x4 micro-tile
@@ -334,11 +442,24 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
     }
 }
 
-int g_tile = 0, g_split = 0;  // tuning overrides (0 = automatic)
+int g_tile = 0, g_split = 0;  // process-wide overrides for sweeps (0 = automatic)
 
 }  // namespace
 
 void gemm_tune(int tile, int split_k) { g_tile = tile; g_split = split_k; }
+int gemm_num_tiles() { return N_TILES; }
+int gemm_tile_rows(int tile) { return tile >= 1 && tile <= N_TILES ? TILE_TM[tile] * 32 : 0; }
+
+GemmConfig gemm_heuristic(int M, int plan_M, int N, int K, size_t ws_bytes) {
+  // The split factor is decided for plan_M rows and then kept for any M, so a row's result does
+  // not depend on how many other rows share the launch; the tile follows the actual M.
+  const int split = pick(std::max(plan_M, M), N, K, ws_bytes, 0).split;
+  return pick(M, N, K, ws_bytes, split);
+}
+
+bool gemm_config_fits(const GemmConfig &c, const GemmArgs &a) {
+  return dispatch(c.tile, a, nullptr, c.split, 1) == hipSuccess;
+}
 
 size_t gemm_workspace_bytes(int M_max) {
   (void)M_max;
@@ -359,30 +480,15 @@ hipError_t launch_pack_weight(const void *w, void *packed, int N, int K, int glu
 }
 
 hipError_t launch_gemm_bf16(const GemmArgs &a, hipStream_t s) {
-  int tile = g_tile;
-  if (tile == 0) {
-    // Rows per workgroup.  Small weight matrices stay resident in L2 / the last-level cache, so
-    // re-reading them for every 32- or 64-row M-tile is cheap and the many small workgroups hide
-    // the per-slice latency better; large ones are streamed once per 160 (or 128) rows.
-    const size_t wbytes = (size_t)a.N * a.K * 2;
-    const size_t MB = 1u << 20;
-    if (a.M <= 32 || wbytes <= 40 * MB) tile = 1;
-    else if (a.M <= 64 || wbytes <= 64 * MB || (a.M <= 160 && wbytes <= 160 * MB)) tile = 2;
-    else if (a.M <= 128) tile = 3;
-    else if (a.M <= 160 || a.M % 160 == 0) tile = 5;
-    else if (a.M % 128 == 0 && a.M <= 512 && a.N >= 65536) tile = 4;
-    else tile = 3;
+  GemmConfig c = {a.tile, a.split};
+  if (c.tile <= 0 || c.split <= 0) {
+    const GemmConfig h = gemm_heuristic(a.M, a.plan_M > 0 ? a.plan_M : a.M, a.N, a.K, a.ws ? a.ws_bytes : 0);
+    if (c.split <= 0) c.split = h.split;
+    if (c.tile <= 0) c.tile = c.split == h.split ? h.tile : pick(a.M, a.N, a.K, a.ws ? a.ws_bytes : 0, c.split).tile;
   }
-  switch (tile) {
-    case 1: return run_wd<1, 1, 4>(a, s, g_split);
-    case 2: return run_wd<2, 1, 4>(a, s, g_split);
-    case 3: return run_wd<4, 1, 3>(a, s, g_split);
-    case 4: return run_wd<4, 2, 2>(a, s, g_split);
-    case 5: return run_wd<5, 1, 3>(a, s, g_split);
-    case 6: return run_wd<5, 2, 1>(a, s, g_split);
-    case 7: return run_wd<2, 2, 3>(a, s, g_split);
-    default: return run_wd<4, 1, 3>(a, s, g_split);
-  }
+  if (g_tile > 0) c.tile = g_tile;
+  if (g_split > 0) c.split = g_split;
+  return dispatch(c.tile, a, s, c.split, 0);
 }
 
 hipError_t launch_gemm_f32(const GemmArgs &a, hipStream_t s) {

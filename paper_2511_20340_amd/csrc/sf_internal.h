@@ -92,11 +92,21 @@ struct GemmArgs {
   int glu;          // bf16 only: w packed with glu=1, y = silu(gate) * up as elem [M][N/2]
   void *ws;         // split-K tickets (first GEMM_TICKET_BYTES, zero between launches) + partial tiles
   size_t ws_bytes;  // 0: no split-K
+  // bf16 kernel choice; 0 = heuristic.  plan_M: the row count the split factor is chosen for (the
+  // largest M this weight is used with), so that every M gets the same K partition; 0 = M.
+  int tile = 0, split = 0, plan_M = 0;
+};
+struct GemmConfig {
+  int tile, split;
 };
 constexpr size_t GEMM_TICKET_BYTES = 64 * 1024;
 constexpr size_t GEMM_PARTIAL_BYTES = 96u * 1024 * 1024;
 size_t gemm_workspace_bytes(int M_max);
 void gemm_tune(int tile, int split_k);  // tuning overrides, 0 = automatic
+int gemm_num_tiles();
+int gemm_tile_rows(int tile);
+GemmConfig gemm_heuristic(int M, int plan_M, int N, int K, size_t ws_bytes);
+bool gemm_config_fits(const GemmConfig &c, const GemmArgs &a);  // split-K partials fit a.ws?
 // bf16 weights are consumed in MFMA-operand-packed form (see gemm.hip); fp32 weights stay row-major
 size_t packed_weight_bytes(int N, int K, int dtype);
 hipError_t launch_pack_weight(const void *w, void *packed, int N, int K, int glu, int dtype, hipStream_t s);
