@@ -300,23 +300,26 @@ def main():
         dt = time.perf_counter() - t
         return dt, int(acc_sum.sum().item())
 
-    # plain autoregressive decoding of the same target through the same engine (k = 0: one token per
-    # sequence per target call), the "W/o SD" row of the paper's tables: timed over the same number of
-    # target calls, then the state is rewound
+    # Plain autoregressive decoding of the same target (the "W/o SD" row of the paper's tables): an
+    # engine of its own with k = 0, so its linear layers are planned for B rows rather than B*(k+1);
+    # same packed weights, a copy of the prefilled target cache, timed over as many target calls.
     ar_ms = None
     if not args.seeded_state and k > 0:
-        keep = {n: getattr(eng, n).clone() for n in ("kv_len", "pending", "n_new", "cu_new", "hooks")}
-        pinned = eng._pinned
-        eng.pin_len_upper(False)
-        eng.len_upper = len0
+        eng0 = Engine(m.cfg(), B, cap, 0)
+        eng0.bind_shared(eng)
+        eng0.tk.copy_(eng.tk)
+        eng0.tv.copy_(eng.tv)
+        eng0.set_state(kv_len=lens, pending=snap["pending"].cpu().numpy(), n_new=np.ones(B, np.int32))
+        eng0.len_upper = len0
         acc1 = torch.empty(B, dtype=torch.int32, device="cuda")
         out1 = torch.empty(B, 1, dtype=torch.int32, device="cuda")
 
         def ar_step():
-            eng.sf_verify_step(0, none, logits_out=lg1)
-            eng.sf_accept_commit(0, none, lg1, accept_out=acc1, tokens_out=out1)
+            eng0.sf_verify_step(0, none, logits_out=lg1)
+            eng0.sf_accept_commit(0, none, lg1, accept_out=acc1, tokens_out=out1)
         if args.graph:
-            eng.pin_len_upper()
+            eng0.pin_len_upper()
+            eng0.len_upper = eng.cap - (k + 1)    # the same attention grid bound as the k-step graph
             ar_step()
             torch.cuda.synchronize()
             g0 = torch.cuda.CUDAGraph()
@@ -333,11 +336,9 @@ def main():
             step0()
         torch.cuda.synchronize()
         ar_ms = 1e3 * (time.perf_counter() - t) / steps
-        for n, t_ in keep.items():
-            getattr(eng, n).copy_(t_)
-        eng.pin_len_upper(pinned)
-        if not pinned:
-            eng.len_upper = len0
+        if args.graph:
+            del g0
+        del eng0
 
     dt_nat, tok_nat = timed_pass(False)
     dt_cal, tok_cal = (dt_nat, tok_nat) if args.seeded_state else timed_pass(True)

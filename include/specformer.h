@@ -211,9 +211,17 @@ sf_status sf_op_linear(const sf_ctx *ctx, const void *x, const void *w, const vo
  * one kernel, gate/up never leave registers; SF_F32: workspace must hold M*2F floats). act: dev elem. */
 sf_status sf_op_linear_swiglu(const sf_ctx *ctx, const void *x, const void *w_gate_up, void *act, int32_t M,
                               int32_t F, int32_t K, void *workspace, size_t workspace_bytes, void *stream);
-/* Tuning aid: force the linear kernels' tile configuration (1..7) and split-K factor; 0 = automatic
- * choice.  Process-wide. host. */
+/* Tuning aid: force the linear kernels' tile configuration (1..sf_linear_num_tiles()) and split-K
+ * factor; 0 = automatic choice.  A forced pair whose partial tiles do not fit the workspace makes the
+ * launch fail with SF_EHIP.  Process-wide. host. */
 sf_status sf_tune_linear(int32_t tile, int32_t split_k);
+int32_t sf_linear_num_tiles(void);
+/* The automatic choice for a bf16 linear layer of M rows whose weight [N][K] is also used with up to
+ * plan_M >= M rows: *split_k is the same for every M <= plan_M (so a row's result does not depend on
+ * the rows batched with it), *tile follows M; *tile_rows = rows per workgroup of that tile.  Pure
+ * host arithmetic, no GPU needed.  host pointers. */
+sf_status sf_linear_config(int32_t M, int32_t plan_M, int32_t N, int32_t K, size_t workspace_bytes,
+                           int32_t *tile, int32_t *split_k, int32_t *tile_rows);
 /* Tuning aid: force the attention's split-KV chunk size in 32-key tiles (>= 16); 0 = automatic. host. */
 sf_status sf_tune_attention(int32_t chunk_tiles);
 

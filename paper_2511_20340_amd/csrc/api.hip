@@ -460,6 +460,16 @@ sf_status sf_tune_linear(int32_t tile, int32_t split_k) {
   return SF_OK;
 }
 
+int32_t sf_linear_num_tiles(void) { return gemm_num_tiles(); }
+
+sf_status sf_linear_config(int32_t M, int32_t plan_M, int32_t N, int32_t K, size_t workspace_bytes, int32_t *tile,
+                           int32_t *split_k, int32_t *tile_rows) {
+  if (M < 1 || plan_M < M || N < 1 || K < 1 || !tile || !split_k || !tile_rows) return SF_EINVAL;
+  const GemmConfig c = gemm_heuristic(M, plan_M, N, K, workspace_bytes);
+  *tile = c.tile; *split_k = c.split; *tile_rows = gemm_tile_rows(c.tile);
+  return SF_OK;
+}
+
 sf_status sf_op_linear(const sf_ctx *c, const void *x, const void *w, const void *bias, const void *residual,
                        void *y, int32_t M, int32_t N, int32_t K, int32_t out_f32, void *workspace,
                        size_t workspace_bytes, void *stream) {

@@ -141,8 +141,8 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const bf16_t 
 }
 
 // The bf16 kernel.  TM 32-row activation blocks x TN weight row blocks per wave, NW waves, ring
-// depth R.  Slot indices are compile-time after unrolling by R; the trip count is a multiple of R
-// (slices past the workgroup's K range contribute zeros).
+// depth R.  Slot indices are compile-time after unrolling by R; the loop runs whole rounds of R
+// slices, and slices past the workgroup's K range contribute zeros.
 template <int TM, int TN, int R, int OCC, int NW>
 __global__ __launch_bounds__(64 * NW, OCC) void gemm_ring_kernel(const bf16_t *__restrict__ A,
                                                         const uint4 *__restrict__ Wp,
@@ -282,15 +282,16 @@ struct Plan {
   size_t partial_bytes, ticket_bytes;
 };
 
-// split_k workgroups share a tile's K range in whole ring rounds (R slices each)
-Plan make_plan(int M, int N, int K, int BM, int BN, int split, int gran) {
+// split_k workgroups share a tile's K range.  The partition depends on K and split only -- never on
+// the tile configuration -- because it fixes the fp32 summation order of every output element.
+Plan make_plan(int M, int N, int K, int BM, int BN, int split) {
   Plan p;
   p.tiles_m = (M + BM - 1) / BM;
   p.tiles_n = (N + BN - 1) / BN;
   const int KT = (K + BK - 1) / BK;
   const int tiles = p.tiles_m * p.tiles_n;
   const int s = split < 1 ? 1 : (split > KT ? KT : split);
-  p.kt_per_split = ((KT + s - 1) / s + gran - 1) / gran * gran;
+  p.kt_per_split = (KT + s - 1) / s;
   p.split_k = (KT + p.kt_per_split - 1) / p.kt_per_split;
   p.partial_bytes = p.split_k > 1 ? (size_t)tiles * p.split_k * BM * BN * sizeof(float) : 0;
   p.ticket_bytes = p.split_k > 1 ? (size_t)tiles * sizeof(unsigned) : 0;
@@ -306,7 +307,7 @@ bool plan_fits(const Plan &p, const void *ws, size_t ws_bytes) {
 template <int TM, int TN, int R, int OCC, int NW>
 hipError_t run_ring(const GemmArgs &a, hipStream_t s, int split, int mode) {
   constexpr int BM = TM * 32, BN = NW * TN * 32;
-  const Plan p = make_plan(a.M, a.N, a.K, BM, BN, split, R);
+  const Plan p = make_plan(a.M, a.N, a.K, BM, BN, split);
   if (!plan_fits(p, a.ws, a.ws_bytes)) return hipErrorInvalidValue;
   if (mode == 1) return hipSuccess;
   const int groups = (p.tiles_n + XCDS - 1) / XCDS;
@@ -364,14 +365,17 @@ GemmConfig pick(int M, int N, int K, size_t ws_bytes, int fixed_split) {
   };
   auto fits = [&](int tm, int split) {
     if (split == 1) return true;
-    const Plan p = make_plan(M, N, K, tm * 32, 128, split, 4);
+    const Plan p = make_plan(M, N, K, tm * 32, 128, split);
     return ws_bytes >= GEMM_TICKET_BYTES + p.partial_bytes && p.ticket_bytes <= GEMM_TICKET_BYTES;
   };
+  auto tiles_of = [&](int tm) { return (M + tm * 32 - 1) / (tm * 32); };
+  auto trim = [&](int tm) {  // fewest padded rows among the block heights with the same tile count
+    while (tm > 1 && tiles_of(tm - 1) == tiles_of(tm)) --tm;
+    return tm;
+  };
   if (fixed_split <= 1) {
-    for (int tm = max_tm; tm >= 1; --tm) {
-      const int tiles_m = (M + tm * 32 - 1) / (tm * 32);
-      if (tiles_m * cols4 >= WG_FULL && reread_ok(tm)) return {with_waves(tm, 1), 1};
-    }
+    for (int tm = max_tm; tm >= 1; --tm)
+      if (tiles_of(tm) * cols4 >= WG_FULL && reread_ok(tm)) return {with_waves(trim(tm), 1), 1};
     if (fixed_split == 1) {
       for (int tm = 1; tm <= max_tm; ++tm)
         if (reread_ok(tm)) return {tm, 1};
@@ -381,25 +385,29 @@ GemmConfig pick(int M, int N, int K, size_t ws_bytes, int fixed_split) {
   // partial tiles cost 8 bytes per output element and split (written, then read): keep that
   // below the weight bytes, and at least 8 K slices per workgroup
   const int split_cap = std::max(1, std::min({16, pow2floor(std::max(1, K / (4 * std::max(M, 1)))), KT / 8}));
-  GemmConfig fallback = {1, 1};
-  for (int tm = max_tm; tm >= 1; --tm) {
-    const int tiles_m = (M + tm * 32 - 1) / (tm * 32);
-    const int wgs = tiles_m * cols4;
+  // weights that stay in L2 are cheap to re-read: there small row blocks come first (less split
+  // for the same number of workgroups); larger ones are tried from the tallest block down
+  const bool small_w = wbytes <= (24u << 20);
+  GemmConfig best = {1, 1};
+  int best_wgs = 0;
+  for (int i = 0; i < max_tm; ++i) {
+    const int tm = small_w ? 1 + i : max_tm - i;
+    const int wgs = tiles_of(tm) * cols4;
     int sp = 1;
     if (fixed_split > 1) {
       sp = fixed_split;
     } else {
-      while (wgs * sp < WG_FULL && sp * 2 <= split_cap) {
+      while (wgs * sp < WG_SPLIT && sp * 2 <= split_cap) {
         if (wgs * sp >= 128 && KT / sp <= 32) break;  // enough workgroups for a short K loop
         sp *= 2;
       }
       while (sp > 1 && !fits(tm, sp)) sp /= 2;
     }
     if (!reread_ok(tm)) continue;
-    fallback = {tm, sp};
-    if (wgs * sp >= WG_SPLIT) return fallback;
+    if (wgs * sp >= WG_SPLIT) return {trim(tm), sp};
+    if (wgs * sp > best_wgs) { best = {tm, sp}; best_wgs = wgs * sp; }
   }
-  return fallback;
+  return best;
 }
 
 // fp32: 64x64 tile, 16 wide k slices, each thread a 4x4 micro-tile

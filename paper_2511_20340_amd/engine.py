@@ -138,6 +138,13 @@ class Engine:
         self._T, self._D = T, D
         sfb.check(self.lib.sf_bind(self.ctx, C.byref(T), C.byref(D) if D is not None else None), "sf_bind")
 
+    def bind_shared(self, other):
+        """Bind the target weights that another engine has already uploaded and packed (no copy,
+        no draft block): for a plain-decoding engine next to a speculative one."""
+        self.w, self._T, self._D = other.w, other._T, None
+        self._keep = other._keep
+        sfb.check(self.lib.sf_bind(self.ctx, C.byref(self._T), None), "sf_bind")
+
     # ---- the three steps ---------------------------------------------------------------------
     def sf_draft_step(self, k, mask=sfb.SF_MASK_BIDIR, draft_out=None, logits_out=None):
         out = draft_out if draft_out is not None else torch.empty(self.B, max(k, 0), dtype=torch.int32, device=self.dev)

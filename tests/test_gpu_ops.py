@@ -94,6 +94,35 @@ def test_linear_bf16(M, N, K):
     assert rel_err(to_np(r), sfo.linear(x, w) + res) < BF16_TOL
 
 
+@pytest.mark.parametrize("M,N,K", [(333, 520, 1792), (160, 264, 2048)])
+def test_linear_bf16_every_tile_and_split_gives_the_same_bits(M, N, K):
+    """The K partition, hence the fp32 summation order, depends on K and the split factor only: every
+    tile configuration must return identical bits, for the whole batch and for a few of its rows."""
+    g = synth.rng(15, M + N)
+    x = synth.to_bf16_values(g.standard_normal((M, K), dtype=np.float32))
+    w = synth.to_bf16_values(g.standard_normal((N, K), dtype=np.float32) * 0.05)
+    ref = sfo.linear(x, w)
+    eng = engine_only(shape_for("bf16", 2, 2, 64), 1, 64, 1)
+    L = sfb.lib()
+    xd, wd = dev(x, "bf16"), dev(w, "bf16")
+    packed = eng.sf_pack_weight(wd)
+    try:
+        for split in (1, 2, 4):
+            first = None
+            for tile in range(1, L.sf_linear_num_tiles() + 1):
+                sfb.check(L.sf_tune_linear(tile, split), "sf_tune_linear")
+                y = eng.sf_op_linear(xd, None, out_f32=True, packed=(packed, N))
+                few = eng.sf_op_linear(xd[:7].contiguous(), None, out_f32=True, packed=(packed, N))
+                torch.cuda.synchronize()
+                assert rel_err(to_np(y), ref) < 1e-5, (tile, split)
+                if first is None:
+                    first = y.clone()
+                assert torch.equal(y, first), (tile, split)
+                assert torch.equal(few, first[:7]), (tile, split)
+    finally:
+        L.sf_tune_linear(0, 0)
+
+
 @pytest.mark.parametrize("M,N,K", [(20, 768, 256), (77, 264, 200), (130, 1024, 1024)])
 def test_linear_f32(M, N, K):
     g = synth.rng(6, M + N)

@@ -1,0 +1,50 @@
+"""Host logic of the linear layers' kernel choice (no GPU): the split-K factor must be the same for
+every row count up to the planned one, since the K partition fixes the fp32 summation order and the
+target's logits for a position may not depend on how many draft positions are verified with it
+(lossless verification, SpecFormer section on draft-then-verify)."""
+import ctypes as C
+
+import pytest
+
+from paper_2511_20340_amd import binding as sfb
+
+WS = (64 << 10) + (96 << 20)
+SHAPES = [(3072, 2048), (2048, 2048), (16384, 2048), (2048, 8192), (32000, 2048),
+          (6144, 4096), (4096, 4096), (28672, 4096), (4096, 14336), (128256, 4096),
+          (7168, 5120), (5120, 5120), (27648, 5120), (5120, 13824), (152064, 5120), (96, 64), (64, 4096)]
+
+
+def config(M, plan, N, K, ws=WS):
+    L = sfb.lib()
+    t, s, r = C.c_int32(), C.c_int32(), C.c_int32()
+    sfb.check(L.sf_linear_config(M, plan, N, K, ws, C.byref(t), C.byref(s), C.byref(r)), "sf_linear_config")
+    return t.value, s.value, r.value
+
+
+@pytest.mark.parametrize("plan", [5, 32, 160, 320, 640, 1280])
+def test_split_is_the_same_for_every_row_count_up_to_the_plan(plan):
+    for N, K in SHAPES:
+        want = config(plan, plan, N, K)[1]
+        for M in sorted({1, 2, 31, 32, 33, plan // 5, plan // 2, plan - 1, plan}):
+            if 1 <= M <= plan:
+                t, s, rows = config(M, plan, N, K)
+                assert s == want, (M, plan, N, K)
+                assert 1 <= t <= sfb.lib().sf_linear_num_tiles() and rows in (32, 64, 96, 128, 160)
+
+
+def test_split_needs_workspace_and_long_k():
+    for N, K in SHAPES:
+        assert config(160, 160, N, K, ws=0)[1] == 1          # nowhere to put partial tiles
+        t, s, _ = config(160, 160, N, K)
+        kt = (K + 63) // 64
+        assert s == 1 or kt // s >= 8                        # at least 8 K slices per workgroup
+        # partial tiles (fp32, at most 160 x N per split) fit the workspace
+        assert s == 1 or s * 160 * ((N + 127) // 128 * 128) * 4 <= 96 << 20
+
+
+def test_rejects_bad_arguments():
+    L = sfb.lib()
+    t = C.c_int32()
+    assert L.sf_linear_config(0, 1, 8, 8, 0, C.byref(t), C.byref(t), C.byref(t)) != 0
+    assert L.sf_linear_config(8, 4, 8, 8, 0, C.byref(t), C.byref(t), C.byref(t)) != 0   # plan < M
+    assert L.sf_linear_config(8, 8, 8, 8, 0, None, C.byref(t), C.byref(t)) != 0
