@@ -118,6 +118,39 @@ def cpu_baseline(wl, seed, budget_s=25.0):
             "ms_per_step_sample": 1e3 * t_used / steps}
 
 
+
+def stream_copy_rate(torch, sfb):
+    """What a plain copy kernel reaches on this GPU (read + write bytes per second), as context for the
+    roofline fractions, which are quoted against the published 8 TB/s."""
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    L = sfb.lib()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(7):
+        if i == 2:
+            e0.record()
+        sfb.check(L.sf_calib_copy(dst.data_ptr(), src.data_ptr(), n, None), "sf_calib_copy")
+    e1.record()
+    torch.cuda.synchronize()
+    s = e0.elapsed_time(e1) * 1e-3 / 5
+    return {"GB/s": round(2 * n / s / 1e9, 1), "what": "1 GiB device-to-device copy kernel, bytes read + written"}
+
+
+def profile_traffic(workload, kernel_class):
+    """HBM bytes per launch of the dominant kernel class as the hardware counters saw them: read from the
+    committed rocprofv3 summary of this workload (FETCH_SIZE / WRITE_SIZE runs scaled by a copy kernel of
+    known size), since counters cannot be collected from inside this process.  None if there is none."""
+    import re
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"step_kernels__{workload}.md")
+    if not os.path.exists(path):
+        return None
+    text = open(path).read()
+    got = [re.search(rf"^traffic_per_launch {re.escape(kernel_class)} {c}: ([0-9.e+]+) bytes", text, re.M)
+           for c in ("FETCH_SIZE", "WRITE_SIZE")]
+    return sum(float(g.group(1)) for g in got) if all(got) else None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -126,6 +159,8 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="index into the baseline's configs (default 1: 1B bf16)")
     ap.add_argument("--k", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--attn-chunk", type=int, default=0,
+                    help="tuning aid: force the attention's split-KV chunk (32-key tiles, >= 16; 0 = automatic)")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--calib-copy", type=int, default=0,
                     help="first run this many plain 1 GiB device copies (reference dispatches for scaling "
@@ -153,6 +188,8 @@ def main():
     es = 2 if m.dtype == "bf16" else 4
     torch.cuda.set_device(0)
 
+    if args.attn_chunk:
+        sfb.check(sfb.lib().sf_tune_attention(args.attn_chunk), "sf_tune_attention")
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -289,16 +326,28 @@ def main():
         else:
             run_eager(n, calibrated)
 
+    step_marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+
     def timed_pass(calibrated):
         run(warm, calibrated)
         torch.cuda.synchronize()
         acc_sum.zero_()
         torch.cuda.synchronize()
         t = time.perf_counter()
-        run(steps, calibrated)
+        if args.graph:                      # one event between replays: the per-step spread
+            for i in range(steps):
+                step_marks[i].record()
+                graphs[calibrated].replay()
+            step_marks[steps].record()
+        else:
+            run(steps, calibrated)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t
-        return dt, int(acc_sum.sum().item())
+        spread = None
+        if args.graph:
+            us = np.array([step_marks[i].elapsed_time(step_marks[i + 1]) for i in range(steps)]) * 1e3
+            spread = {q: round(float(np.percentile(us, p)), 1) for q, p in (("p10", 10), ("p50", 50), ("p90", 90))}
+        return dt, int(acc_sum.sum().item()), spread
 
     # Plain autoregressive decoding of the same target (the "W/o SD" row of the paper's tables): an
     # engine of its own with k = 0, so its linear layers are planned for B rows rather than B*(k+1);
@@ -340,8 +389,8 @@ def main():
             del g0
         del eng0
 
-    dt_nat, tok_nat = timed_pass(False)
-    dt_cal, tok_cal = (dt_nat, tok_nat) if args.seeded_state else timed_pass(True)
+    dt_nat, tok_nat, spread_nat = timed_pass(False)
+    dt_cal, tok_cal, _ = (dt_nat, tok_nat, None) if args.seeded_state else timed_pass(True)
 
     result = {
         "metric": "accepted tokens/s at batch B (draft+verify+accept step)",
@@ -357,6 +406,7 @@ def main():
                    "launch": "one HIP graph replay per step" if args.graph else "eager launches"},
         "kappa": tok_nat / (steps * B),
         "step_us": 1e6 * dt_nat / steps,
+        "step_us_spread": spread_nat,      # per-replay, HIP events between graph replays (None when eager)
         "calibrated": {"what": "draft tokens replaced after sf_draft_step by the target's greedy continuation, "
                                "each slot corrupted with probability 1-alpha, so kappa matches the paper's model class",
                        "kappa_target": kappa_t, "alpha": alpha, "kappa": tok_cal / (steps * B),
@@ -402,6 +452,9 @@ def main():
                   "verify_us": np.mean([e[1].elapsed_time(e[2]) for e in ev]) * 1e3,
                   "accept_us": np.mean([e[2].elapsed_time(e[3]) for e in ev]) * 1e3}
         result["phase_us_profiled_pass"] = {a: round(float(b), 1) for a, b in phases.items()}
+        eager_us = np.array([e[0].elapsed_time(e[3]) for e in ev]) * 1e3
+        result["step_us_eager_profiled"] = {q: round(float(np.percentile(eager_us, p)), 1)
+                                            for q, p in (("p10", 10), ("p50", 50), ("p90", 90))}
         qm = k + 1
         shapes = gemm_shapes(m, B, k, qm)
         g_bytes, g_flops = gemm_work(shapes, es)
@@ -444,10 +497,11 @@ def main():
         roof.update({"kernel": dom, "avg_launch_us": e["avg_us"], "launches_per_step": e["launches_per_step"],
                      "algorithmic_per_launch": (e.get("bytes_per_step", 0.0) if roof["unit"] == "GB/s" else
                                                 e.get("flops_per_step", 0.0)) / e["launches_per_step"],
-                     "traffic": None,
+                     "traffic": profile_traffic(wl.name, dom),
                      "how": "HIP events around every launch of the class on the launch stream, same steps as the timed pass"})
         result["roofline"] = roof
 
+    result["hbm_stream_copy_measured"] = stream_copy_rate(torch, sfb)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, wl.seed)
     print(json.dumps(result))

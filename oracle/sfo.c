@@ -260,12 +260,21 @@ int sfo_verify_step(const sfo_cfg *c, const sfo_target_weights *w, sfo_state *s,
  *     position-specific slot states (second equation).
  *  4. The slots run one pre-norm attention + SwiGLU layer (Draft Bi-directional Attention);
  *     a slot sees the whole cached context and, with BIDIR, all k slots.
- *  5. Output norm, the target's LM head, argmax. */
+ *  5. Output norm, the target's LM head, argmax.
+ *
+ * With SFO_DRAFT_TWO_STAGE in mask_mode the two attentions stay apart as the section writes them
+ * (its first and third equations): the context attention is a residual unit of its own,
+ * I_D = X + MSA(RMS(X)), causal over the cached context, and only its newest row feeds the
+ * Positional FFN; the slot attention then sees the k slots only (positions 0..k-1, no cached
+ * keys) and has its own norm, QKV and output weights. */
 int sfo_draft_step(const sfo_cfg *c, const sfo_draft_weights *w, const float *lm_head, sfo_state *s,
                    int k, int mask_mode, int32_t *draft, double *draft_logits) {
   int B = s->B, d = c->d_model, Hq = c->n_q_heads, Hkv = c->n_kv_heads, hd = c->head_dim;
   int V = c->vocab, R = c->round_bf16, cap = s->cap;
   int NQ = Hq * hd, NKV = Hkv * hd, N = NQ + 2 * NKV;
+  int two_stage = (mask_mode & SFO_DRAFT_TWO_STAGE) != 0;
+  mask_mode &= ~SFO_DRAFT_TWO_STAGE;
+  if (two_stage && (!w->sa_norm || !w->sa_wqkv || !w->sa_wo)) return -1;
   if (k < 1) return 0;
   for (int b = 0; b < B; ++b) {
     if (s->n_new[b] < 0 || s->n_new[b] > s->q_max || s->n_new[b] > s->kv_len[b]) return -1;
@@ -303,6 +312,22 @@ int sfo_draft_step(const sfo_cfg *c, const sfo_draft_weights *w, const float *lm
         memcpy(s->dv + dst, qkv + (long)r * N + NQ + NKV + (long)g * hd, sizeof(double) * hd);
       }
     memcpy(xlast + (long)b * d, x + (long)(n - 1) * d, sizeof(double) * d);
+    if (two_stage) {
+      /* the context attention's own output at the newest row: its query against every cached
+       * context key up to and including itself, projected and added to the row (residual) */
+      double *q = dalloc(NQ), *o = dalloc(NQ), *proj = dalloc(d);
+      int32_t last_pos = pos[n - 1], before = last_pos; /* keys before the row = its position */
+      memcpy(q, qkv + (long)(n - 1) * N, sizeof(double) * NQ);
+      sfo_rope(q, &last_pos, 1, Hq, hd, c->rope_theta);
+      round_buf(q, NQ, R);
+      sfo_attention(q, s->dk + (long)b * Hkv * cap * hd, s->dv + (long)b * Hkv * cap * hd, &before, 1, 1, Hq, Hkv,
+                    hd, cap, SFO_MASK_CAUSAL, o);
+      round_buf(o, NQ, R);
+      sfo_linear(o, w->wo, NULL, 1, NQ, d, proj);
+      for (int e = 0; e < d; ++e) xlast[(long)b * d + e] += proj[e];
+      round_buf(xlast + (long)b * d, d, R);
+      free(q); free(o); free(proj);
+    }
     free(f); free(x); free(a); free(qkv); free(kk); free(pos);
   }
   /* step 3 */
@@ -313,7 +338,15 @@ int sfo_draft_step(const sfo_cfg *c, const sfo_draft_weights *w, const float *lm
   sfo_linear(an, w->w_pos, w->b_pos, B, d, k * d, S); /* row b = [slot0 | slot1 | ...] = rows b*k+s of S */
   round_buf(S, (long)M * d, R);
   /* step 4 */
-  attn_half(c, w->attn_norm, w->wqkv, w->wo, S, B, k, s->kv_len, cap, s->dk, s->dv, mask_mode);
+  if (two_stage) {
+    /* the slots alone: an empty prefix in a k-slot cache of their own */
+    int32_t *len0 = (int32_t *)calloc((size_t)B, sizeof(int32_t));
+    double *kc2 = dalloc((long)B * Hkv * k * hd), *vc2 = dalloc((long)B * Hkv * k * hd);
+    attn_half(c, w->sa_norm, w->sa_wqkv, w->sa_wo, S, B, k, len0, k, kc2, vc2, mask_mode);
+    free(len0); free(kc2); free(vc2);
+  } else {
+    attn_half(c, w->attn_norm, w->wqkv, w->wo, S, B, k, s->kv_len, cap, s->dk, s->dv, mask_mode);
+  }
   ffn_half(c, w->ffn_norm, w->w_gate, w->w_up, w->w_down, S, M);
   /* step 5 */
   sfo_rmsnorm(S, w->out_norm, M, d, c->rms_eps, o);

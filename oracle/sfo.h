@@ -35,6 +35,10 @@ extern "C" {
 #endif
 
 enum { SFO_MASK_CAUSAL = 0, SFO_MASK_BIDIR = 1 };
+/* OR-ed into the draft step's mask mode: the two attentions of the SpecFormer section kept apart
+ * (Context Causal Attention with its own output, then a prefix-free Draft Bi-directional Attention
+ * with a parameter set of its own) instead of one attention over cached context + slots. */
+enum { SFO_DRAFT_TWO_STAGE = 16 };
 
 typedef struct {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
@@ -68,6 +72,10 @@ typedef struct {
   const float *w_gate, *w_up; /* [F][d] */
   const float *w_down;     /* [d][F] */
   const float *out_norm;   /* [d] */
+  /* two-stage wiring only (may be NULL otherwise): the slot attention's own parameters */
+  const float *sa_norm;    /* [d] */
+  const float *sa_wqkv;    /* [(Hq+2Hkv)*hd][d] */
+  const float *sa_wo;      /* [d][Hq*hd] */
 } sfo_draft_weights;
 
 typedef struct {

@@ -11,6 +11,7 @@ import numpy as np
 from . import build as _build
 
 MASK_CAUSAL, MASK_BIDIR = 0, 1
+DRAFT_TWO_STAGE = 16   # OR-ed into draft_step's mask_mode: context attention and slot attention kept apart
 
 _f = C.POINTER(C.c_float)
 _d = C.POINTER(C.c_double)
@@ -33,7 +34,7 @@ class TargetW(C.Structure):
 class DraftW(C.Structure):
     _fields_ = [(n, _f) for n in
                 ("group_norm", "w_ds", "pos_norm", "w_pos", "b_pos", "attn_norm", "wqkv", "wo",
-                 "ffn_norm", "w_gate", "w_up", "w_down", "out_norm")]
+                 "ffn_norm", "w_gate", "w_up", "w_down", "out_norm", "sa_norm", "sa_wqkv", "sa_wo")]
 
 
 class State(C.Structure):
@@ -187,6 +188,8 @@ class Oracle:
         if dw is not None:
             self.dw = DraftW()
             for name, _t in DraftW._fields_:
+                if name.startswith("sa_") and name not in dw:      # two-stage wiring not used
+                    continue
                 a = _c32(dw[name]); self._keep.append(a); setattr(self.dw, name, _fp(a))
         shp = (B, self.Hkv, cap, self.hd)
         self.tk = np.zeros((L,) + shp); self.tv = np.zeros((L,) + shp)

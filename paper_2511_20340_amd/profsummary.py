@@ -13,6 +13,11 @@ import csv
 import re
 
 
+# kernel classes as bench.py names them -> pattern over the kernel names
+CLASSES = {"linear": r"gemm_(ring|f32)_kernel", "attention": r"attn_(bf16|f32)_kernel", "argmax": r"argmax_partial",
+           "rmsnorm": r"rmsnorm_kernel", "rope_kv_append": r"rope_kv_kernel"}
+
+
 def short(name):
     name = re.sub(r"\(anonymous namespace\)::", "", name)
     name = re.sub(r"^void ", "", name)
@@ -56,7 +61,15 @@ def pmc(path, counter, calib_kernel, calib_bytes, cmd):
     for k, vs in sorted(per.items(), key=lambda kv: -sum(kv[1])):
         m = sum(vs) / len(vs)
         out.append("| %s | %d | %.1f | %.4g |" % (k, len(vs), m, m * scale))
-    return "\n".join(out[:40])
+    out = out[:40]
+    # per kernel class, what bench.py reads back as roofline.traffic (dispatch-weighted mean)
+    out.append("")
+    for cls, pat in CLASSES.items():
+        vs = [v for k, vals in per.items() if re.search(pat, k) for v in vals]
+        if vs:
+            out.append(f"traffic_per_launch {cls} {counter}: {sum(vs) / len(vs) * scale:.6g} bytes "
+                       f"(mean of {len(vs)} dispatches)")
+    return "\n".join(out)
 
 
 def main():

@@ -126,6 +126,10 @@ def draft_weights(m: ModelShape, k_max, seed, std=0.02):
         "w_up": _normal(seed, s + 7, (F, d), std, m.dtype),
         "w_down": _normal(seed, s + 8, (d, F), std, m.dtype),
         "out_norm": np.ones(d, np.float32),
+        # the slot attention's own parameter set (two-stage wiring of the draft block)
+        "sa_norm": np.ones(d, np.float32),
+        "sa_wqkv": _normal(seed, s + 9, (nqkv, d), std, m.dtype),
+        "sa_wo": _normal(seed, s + 10, (d, m.n_q_heads * hd), std, m.dtype),
     }
 
 

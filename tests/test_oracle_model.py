@@ -11,7 +11,7 @@ import torch.nn.functional as F
 
 import synth
 from oracle import sfo
-from oracle.sfo import MASK_BIDIR, MASK_CAUSAL
+from oracle.sfo import DRAFT_TWO_STAGE, MASK_BIDIR, MASK_CAUSAL
 
 SHAPE = synth.ModelShape("pin", 3, 32, 4, 2, 8, 48, 61, "f32")   # odd L: hooks at 0, 1, 2, 3
 K_MAX = 4
@@ -178,6 +178,109 @@ def test_draft_incremental_context_equals_one_shot():
             L = SHAPE.n_layers
             hooks = np.stack([hs[0], hs[L // 2], hs[L - 1], hs[L]], 1)
             np.testing.assert_allclose(dl[b], t_draft(dw, tw["lm_head"], hooks, k), rtol=1e-7, atol=1e-9)
+
+
+def t_draft_two_stage(dw, lm_head, hooks, k, bidir=True):
+    """The draft block with its two attentions kept apart (first and third equation of the SpecFormer
+    section), composed from torch library ops: I_D = X + MSA(RMS(X)) causal over the context, slots
+    from the newest row of I_D, then self-attention over the k slots alone with its own weights."""
+    m = SHAPE
+    n, d = hooks.shape[0], m.d_model
+    nq, nkv = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim
+
+    def attn(x, norm, wqkv, wo, causal):
+        t = x.shape[0]
+        pos = torch.arange(t)
+        a = F.rms_norm(x, (d,), T(norm), m.rms_eps)
+        qkv = F.linear(a, T(wqkv))
+        q = t_rope(qkv[:, :nq].view(-1, m.n_q_heads, m.head_dim), pos, m.rope_theta)
+        kk = t_rope(qkv[:, nq:nq + nkv].view(-1, m.n_kv_heads, m.head_dim), pos, m.rope_theta)
+        v = qkv[:, nq + nkv:].view(-1, m.n_kv_heads, m.head_dim)
+        o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], kk.transpose(0, 1)[None],
+                                           v.transpose(0, 1)[None], is_causal=causal, enable_gqa=True)
+        return x + F.linear(o[0].transpose(0, 1).reshape(t, nq), T(wo))
+    f = torch.stack([F.rms_norm(T(hooks[:, g]), (d,), T(dw["group_norm"][g]), m.rms_eps) for g in range(4)], 1)
+    x = F.linear(f.reshape(n, 4 * d), T(dw["w_ds"]))
+    i_d = attn(x, dw["attn_norm"], dw["wqkv"], dw["wo"], True)
+    s0 = F.linear(F.rms_norm(i_d[-1], (d,), T(dw["pos_norm"]), m.rms_eps), T(dw["w_pos"])[:k * d],
+                  T(dw["b_pos"])[:k * d]).view(k, d)
+    s1 = attn(s0, dw["sa_norm"], dw["sa_wqkv"], dw["sa_wo"], not bidir)
+    a = F.rms_norm(s1, (d,), T(dw["ffn_norm"]), m.rms_eps)
+    s2 = s1 + F.linear(F.silu(F.linear(a, T(dw["w_gate"]))) * F.linear(a, T(dw["w_up"])), T(dw["w_down"]))
+    return F.linear(F.rms_norm(s2, (d,), T(dw["out_norm"]), m.rms_eps), T(lm_head)).numpy()
+
+
+@pytest.mark.parametrize("bidir", [True, False])
+def test_two_stage_draft_matches_torch_composition(bidir):
+    tw, dw = weights()
+    lens = [7, 12]
+    prompts = synth.prompts(lens, SHAPE.vocab, 5)
+    o = new_oracle(tw, dw, 2)
+    o.prefill(prompts)
+    k = K_MAX
+    mode = (MASK_BIDIR if bidir else MASK_CAUSAL) | DRAFT_TWO_STAGE
+    draft, lg = o.draft_step(k, mode, want_logits=True)
+    for b, p in enumerate(prompts):
+        _, hs = t_target(tw, p)
+        L = SHAPE.n_layers
+        hooks = np.stack([hs[0], hs[L // 2], hs[L - 1], hs[L]], 1)
+        want = t_draft_two_stage(dw, tw["lm_head"], hooks, k, bidir)
+        np.testing.assert_allclose(lg[b], want, rtol=1e-8, atol=1e-10)
+        np.testing.assert_array_equal(draft[b], want.argmax(-1))
+    # and it is not the single-attention wiring in disguise
+    o2 = new_oracle(tw, dw, 2); o2.prefill(prompts)
+    _, lg_h = o2.draft_step(k, MASK_BIDIR if bidir else MASK_CAUSAL, want_logits=True)
+    assert not np.allclose(lg_h, lg)
+
+
+def test_two_stage_draft_incremental_context_equals_one_shot():
+    """The context attention of the two-stage wiring reads the draft layer's KV cache: feeding the
+    committed rows step by step equals recomputing the whole context."""
+    tw, dw = weights()
+    prompts = synth.prompts([8, 5], SHAPE.vocab, 6)
+    k = 3
+    o = new_oracle(tw, dw, 2)
+    o.prefill(prompts)
+    o.draft_step(k, MASK_BIDIR | DRAFT_TWO_STAGE)
+    rs = np.random.default_rng(2)
+    seqs = [list(p) for p in prompts]
+    for _ in range(3):
+        d = rs.integers(0, SHAPE.vocab, (2, k)).astype(np.int32)
+        lg = o.verify_step(k, d)
+        pend = o.pending.copy()
+        acc, _ = o.accept_commit(k, d, lg, force_len=rs.integers(1, k + 2, 2))
+        for b in range(2):
+            seqs[b] += ([int(pend[b])] + list(d[b]))[:acc[b]]
+        _, dl = o.draft_step(k, MASK_BIDIR | DRAFT_TWO_STAGE, want_logits=True)
+        for b in range(2):
+            _, hs = t_target(tw, seqs[b])
+            L = SHAPE.n_layers
+            hooks = np.stack([hs[0], hs[L // 2], hs[L - 1], hs[L]], 1)
+            np.testing.assert_allclose(dl[b], t_draft_two_stage(dw, tw["lm_head"], hooks, k), rtol=1e-7, atol=1e-9)
+
+
+def test_two_stage_slots_do_not_see_the_context_keys_directly():
+    """In the two-stage wiring the context reaches the slots only through the newest row of I_D.
+    With W_P zeroed the slot states are b_P alone, and since the slot attention has no cached keys
+    the draft then cannot depend on the context at all; the single hybrid attention still reads the
+    draft cache and does."""
+    tw, dw = weights()
+    k = 3
+    dw0 = dict(dw)
+    dw0["w_pos"] = np.zeros_like(dw["w_pos"])
+    outs = []
+    for seed in (11, 12):
+        prompts = synth.prompts([5, 9], SHAPE.vocab, seed)
+        o = new_oracle(tw, dw0, 2); o.prefill(prompts)
+        outs.append(o.draft_step(k, MASK_BIDIR | DRAFT_TWO_STAGE, want_logits=True)[1])
+    np.testing.assert_array_equal(outs[0], outs[1])          # slots = b_P only: context-free
+    np.testing.assert_array_equal(outs[0][0], outs[0][1])    # and the same for every sequence
+    outs_h = []
+    for seed in (11, 12):
+        prompts = synth.prompts([5, 9], SHAPE.vocab, seed)
+        o = new_oracle(tw, dw0, 2); o.prefill(prompts)
+        outs_h.append(o.draft_step(k, MASK_BIDIR, want_logits=True)[1])
+    assert not np.allclose(outs_h[0], outs_h[1])             # one hybrid attention still reads the cache
 
 
 def test_positional_ffn_slots_use_their_own_rows_of_w_pos():
