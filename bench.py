@@ -38,7 +38,7 @@ def solve_alpha(kappa, k):
     return 0.5 * (lo + hi)
 
 
-def device_weights(m, k, seed, torch):
+def device_weights(m, k, seed, torch, two_stage=False):
     """Random-init weights generated directly on the GPU (N(0, 0.02^2), norm gains 1)."""
     g = torch.Generator(device="cuda")
     g.manual_seed(seed)
@@ -58,10 +58,12 @@ def device_weights(m, k, seed, torch):
     dw = {"group_norm": ones(4, d), "w_ds": rnd(d, 4 * d), "pos_norm": ones(d), "w_pos": rnd(max(k, 1) * d, d),
           "b_pos": rnd(max(k, 1) * d), "attn_norm": ones(d), "wqkv": rnd(nqkv, d), "wo": rnd(d, m.n_q_heads * hd),
           "ffn_norm": ones(d), "w_gate_up": rnd(2 * F, d), "w_down": rnd(d, F), "out_norm": ones(d)}
+    if two_stage:      # the slot attention's own parameter set
+        dw.update({"sa_norm": ones(d), "sa_wqkv": rnd(nqkv, d), "sa_wo": rnd(d, m.n_q_heads * hd)})
     return tw, dw
 
 
-def gemm_shapes(m, B, k, qm):
+def gemm_shapes(m, B, k, qm, two_stage=False):
     """(M, N, K, out_bytes_per_elem, has_residual) of every linear launch in one step."""
     es = 2 if m.dtype == "bf16" else 4
     d, F, V = m.d_model, m.d_ffn, m.vocab
@@ -72,6 +74,8 @@ def gemm_shapes(m, B, k, qm):
     out = layer(M) * m.n_layers + [(M, V, d, 4, 0)]
     if k > 0:
         out += [(Mh, d, 4 * d, es, 0), (Mh, 2 * nkv, d, es, 0), (B, k * d, d, es, 0)] + layer(Ms) + [(Ms, V, d, 4, 0)]
+        if two_stage:   # query and output projection of the context attention's newest row
+            out += [(B, nq, d, es, 0), (B, d, nq, es, 1)]
     return out
 
 
@@ -158,6 +162,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=1, help="index into the baseline's configs (default 1: 1B bf16)")
     ap.add_argument("--k", type=int, default=None)
+    ap.add_argument("--draft-wiring", choices=["hybrid", "two-stage"], default="hybrid",
+                    help="hybrid: one draft attention over cached context + slots (default); two-stage: context "
+                         "attention and slot attention kept apart, as the SpecFormer section writes them")
+    ap.add_argument("--draft-mask", choices=["bidir", "causal"], default="bidir",
+                    help="mask inside the slot block (causal = the paper's '+Att Mask' ablation)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-chunk", type=int, default=0,
                     help="tuning aid: force the attention's split-KV chunk (32-key tiles, >= 16; 0 = automatic)")
@@ -205,7 +214,10 @@ def main():
     total_steps = n_pass * (steps + warm) + 6
     cap = synth.kv_capacity(int(lens.max()), total_steps, k)
     eng = Engine(m.cfg(), B, cap, k)
-    tw, dw = device_weights(m, k, wl.seed, torch)
+    two_stage = args.draft_wiring == "two-stage"
+    draft_mode = (sfb.SF_MASK_BIDIR if args.draft_mask == "bidir" else sfb.SF_MASK_CAUSAL) | \
+        (sfb.SF_DRAFT_TWO_STAGE if two_stage else 0)
+    tw, dw = device_weights(m, k, wl.seed, torch, two_stage)
     eng.bind(tw, dw)
     del tw, dw
 
@@ -265,7 +277,7 @@ def main():
 
     def one_step(calibrated):
         """draft -> (optional draft replacement) -> verify -> accept; everything on the current stream"""
-        eng.sf_draft_step(k, draft_out=draft)
+        eng.sf_draft_step(k, mask=draft_mode, draft_out=draft)
         if calibrated and k > 0:
             idx = (eng.kv_len.to(torch.int64) - len_t + 1)[:, None] + slot
             draft.copy_(torch.gather(inj, 1, idx.clamp_(max=n_ar - 1)))
@@ -277,7 +289,7 @@ def main():
         for i in range(n):
             if phase_ev is not None:
                 phase_ev[i][0].record()
-            eng.sf_draft_step(k, draft_out=draft)
+            eng.sf_draft_step(k, mask=draft_mode, draft_out=draft)
             if calibrated and k > 0:
                 idx = (eng.kv_len.to(torch.int64) - len_t + 1)[:, None] + slot
                 draft.copy_(torch.gather(inj, 1, idx.clamp_(max=n_ar - 1)))
@@ -400,7 +412,7 @@ def main():
         "config": {"workload": wl.name, "baseline_config_index": args.config, "batch": B, "k": k,
                    "prefix": [int(wl.prefix_lo), int(wl.prefix_hi)], "layers": m.n_layers, "d_model": m.d_model,
                    "q_heads": m.n_q_heads, "kv_heads": m.n_kv_heads, "head_dim": m.head_dim, "d_ffn": m.d_ffn,
-                   "vocab": m.vocab, "drafts": "natural (the random-init draft block's own tokens)",
+                   "vocab": m.vocab, "draft_wiring": args.draft_wiring, "draft_mask": args.draft_mask, "drafts": "natural (the random-init draft block's own tokens)",
                    "state": "seeded caches (no prefill)" if args.seeded_state else
                             "real chunked prefill through sf_verify_step", "prefill_s": round(t_prefill, 3),
                    "launch": "one HIP graph replay per step" if args.graph else "eager launches"},
@@ -456,12 +468,15 @@ def main():
         result["step_us_eager_profiled"] = {q: round(float(np.percentile(eager_us, p)), 1)
                                             for q, p in (("p10", 10), ("p50", 50), ("p90", 90))}
         qm = k + 1
-        shapes = gemm_shapes(m, B, k, qm)
+        shapes = gemm_shapes(m, B, k, qm, two_stage)
         g_bytes, g_flops = gemm_work(shapes, es)
         lsum = len_hist.to(torch.float64).sum(1).cpu().numpy()        # sum_b kv_len per step
         kvb = 2 * m.head_dim * es * m.n_kv_heads
         att_v = m.n_layers * (kvb * (lsum + B * (k + 1)) + 2 * B * (k + 1) * m.n_q_heads * m.head_dim * es)
         att_d = (kvb * (lsum + B * k) + 2 * B * k * m.n_q_heads * m.head_dim * es) if k > 0 else 0 * lsum
+        if two_stage and k > 0:   # one context row over the cache, then the k slots among themselves
+            att_d = (kvb * lsum + 2 * B * m.n_q_heads * m.head_dim * es) + \
+                    (kvb * B * k + 2 * B * k * m.n_q_heads * m.head_dim * es)
         att_bytes = float(np.mean(att_v + att_d))
         att_flops = float(np.mean(4.0 * m.n_q_heads * m.head_dim *
                                   (m.n_layers * (k + 1) * (lsum + B * (k + 1)) + k * (lsum + B * k))))

@@ -54,6 +54,13 @@ typedef enum { SF_BF16 = 0, SF_F32 = 1 } sf_dtype;
  * along the draft).  Cached prefix positions are always visible.  CAUSAL: block row i sees block
  * keys j <= i (verify pass; the "+Att Mask" ablation of the draft).  BIDIR: every block key. */
 typedef enum { SF_MASK_CAUSAL = 0, SF_MASK_BIDIR = 1 } sf_mask_mode;
+/* OR-ed into sf_draft_step's mask argument: run the draft block with its two attentions kept apart,
+ * as the SpecFormer section writes them (first and third equation): the Context Causal Attention is
+ * a residual unit of its own, I_D = X + MSA(RMS(X)), whose newest row feeds the Positional FFN, and
+ * the Draft Bi-directional Attention then sees the k slots only (positions 0..k-1, no cached keys)
+ * with the parameter set sa_* of sf_draft_weights.  Without the flag one attention layer serves both:
+ * the slots attend to the cached context and to each other. */
+enum { SF_DRAFT_TWO_STAGE = 16 };
 
 /* A pre-norm decoder with grouped-query attention, rotary embedding (rotate-half pairing) and a
  * SwiGLU feed-forward.  The draft block uses the same widths with n_layers = 1. */
@@ -91,6 +98,10 @@ typedef struct {
   const void *w_gate_up;  /* [2F][d]  packed with glu = 1                                          */
   const void *w_down;     /* [d][F]                                                                */
   const void *out_norm;   /* [d]  the draft's own output norm; logits use the target's lm_head     */
+  /* SF_DRAFT_TWO_STAGE only, NULL otherwise: the slot attention's own parameters                  */
+  const void *sa_norm;    /* [d]                                                                   */
+  const void *sa_wqkv;    /* [(Hq+2Hkv)*hd][d]  packed                                             */
+  const void *sa_wo;      /* [d][Hq*hd]         packed                                             */
 } sf_draft_weights;
 
 /* Decoding state, every buffer dev and caller-owned.  Per sequence b:

@@ -8,6 +8,7 @@ LIB_PATH = os.path.join(HERE, "libspecformer.so")
 SF_OK, SF_EINVAL, SF_ECAPACITY, SF_ESTATE, SF_EHIP, SF_EUNSUPPORTED = range(6)
 SF_BF16, SF_F32 = 0, 1
 SF_MASK_CAUSAL, SF_MASK_BIDIR = 0, 1
+SF_DRAFT_TWO_STAGE = 16   # OR-ed into sf_draft_step's mask
 KERNEL_CLASSES = ["linear", "attention", "attention_combine", "rmsnorm", "rope_kv_append", "silu_mul",
                   "embed_hook", "argmax", "accept"]
 
@@ -33,7 +34,7 @@ class TargetWeights(C.Structure):
 
 class DraftWeights(C.Structure):
     _fields_ = [(n, vp) for n in ("group_norm", "w_ds", "pos_norm", "w_pos", "b_pos", "attn_norm", "wqkv", "wo",
-                                  "ffn_norm", "w_gate_up", "w_down", "out_norm")]
+                                  "ffn_norm", "w_gate_up", "w_down", "out_norm", "sa_norm", "sa_wqkv", "sa_wo")]
 
 
 class State(C.Structure):

@@ -6,6 +6,8 @@
 #include <vector>
 #include "sf_internal.h"
 
+#include <cstddef>
+
 using namespace sf;
 
 // Optional per-kernel-class timing (sf_profile_begin / sf_profile_end): every launch is bracketed
@@ -41,6 +43,7 @@ size_t esize(int dtype) { return dtype == SF_BF16 ? 2 : 4; }
 struct Arena {
   size_t h, a, qkv, qr, ao, gu, act, table, part_o, part_ml, pmax, pidx;  // shared
   size_t f4, x, kvc, xl, s0, dlogits;                                    // draft only
+  size_t x_last, id_last, q1, qr1, ao1, len_m1, zeros, kc2, vc2;         // draft, two-stage wiring
   size_t gemm_ws, gemm_ws_bytes;
   size_t total;
 };
@@ -60,6 +63,7 @@ Arena plan(const sf_ctx *c, int B, int k, int cap) {
   // between calls, so no other buffer of any call shape may ever overlap them
   a.gemm_ws_bytes = m.dtype == SF_BF16 ? gemm_workspace_bytes((int)Mx) : 0;
   a.gemm_ws = take(a.gemm_ws_bytes);
+  a.zeros = take((size_t)B * sizeof(int32_t));  // likewise never written: the empty prefix of a slot-only attention
   a.h = take(M * d * es);
   a.a = take(Mx * d * es);
   a.qkv = take(M * (nq + 2 * nkv) * es);
@@ -81,6 +85,14 @@ Arena plan(const sf_ctx *c, int B, int k, int cap) {
   a.xl = take((size_t)B * d * es);
   a.s0 = take(Ms * d * es);
   a.dlogits = take(Ms * V * sizeof(float));
+  a.x_last = take((size_t)B * d * es);
+  a.id_last = take((size_t)B * d * es);
+  a.q1 = take((size_t)B * nq * es);
+  a.qr1 = take((size_t)B * nq * es);
+  a.ao1 = take((size_t)B * nq * es);
+  a.len_m1 = take((size_t)B * sizeof(int32_t));
+  a.kc2 = take((size_t)B * nkv * TK * es);      // one 32-key tile per (sequence, kv head)
+  a.vc2 = take((size_t)B * nkv * TK * es);
   a.total = off;
   return a;
 }
@@ -246,9 +258,12 @@ sf_status sf_bind(sf_ctx *c, const sf_target_weights *t, const sf_draft_weights 
     if (!t->attn_norm[l] || !t->wqkv[l] || !t->wo[l] || !t->ffn_norm[l] || !t->w_gate_up[l] || !t->w_down[l])
       return SF_EINVAL;
   if (d) {
+    // every pointer up to out_norm is required; the slot attention's own set (sa_*) comes whole or not at all
     const void *const *p = reinterpret_cast<const void *const *>(d);
-    for (size_t i = 0; i < sizeof(sf_draft_weights) / sizeof(void *); ++i)
+    for (size_t i = 0; i < offsetof(sf_draft_weights, sa_norm) / sizeof(void *); ++i)
       if (!p[i]) return SF_EINVAL;
+    const int n_sa = (d->sa_norm != nullptr) + (d->sa_wqkv != nullptr) + (d->sa_wo != nullptr);
+    if (n_sa != 0 && n_sa != 3) return SF_EINVAL;
   }
   c->tw = *t;
   c->attn_norm.assign(t->attn_norm, t->attn_norm + L);
@@ -317,20 +332,25 @@ sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, 
   sf_status v = check_state(c, st, k, true);
   if (v != SF_OK) return v;
   if (k == 0) return SF_OK;
+  const bool two_stage = (mask & SF_DRAFT_TWO_STAGE) != 0;
+  mask &= ~SF_DRAFT_TWO_STAGE;
   if (!draft_tokens || len_upper < 0 || (mask != SF_MASK_CAUSAL && mask != SF_MASK_BIDIR)) return SF_EINVAL;
   const sf_model_cfg &m = c->dc;
   const int B = st->B, cap = st->cap, qm = c->max_k + 1, Mh = B * qm, Ms = B * k;
   if ((long)len_upper + k > cap) return SF_ECAPACITY;
   if ((v = check_attn_shape(m, k)) != SF_OK) return v;
+  const sf_draft_weights &w = c->dw;
+  if (two_stage && (!w.sa_norm || !w.sa_wqkv || !w.sa_wo)) return SF_ESTATE;
+  if (two_stage && k > TK) return SF_EUNSUPPORTED;
   const Arena A = plan(c, B, k, cap);
   char *ws = (char *)st->workspace;
   void *a = ws + A.a, *qkv = ws + A.qkv, *qr = ws + A.qr, *ao = ws + A.ao, *act = ws + A.act;
   void *f4 = ws + A.f4, *x = ws + A.x, *kvc = ws + A.kvc, *xl = ws + A.xl, *s0 = ws + A.s0;
   float *gu = (float *)(ws + A.gu), *dlogits = draft_logits ? draft_logits : (float *)(ws + A.dlogits);
+  float *part_o = (float *)(ws + A.part_o), *part_ml = (float *)(ws + A.part_ml);
   const int d = m.d_model, F = m.d_ffn;
   const int nq = m.n_q_heads * m.head_dim, nkv = m.n_kv_heads * m.head_dim;
   const size_t es = esize(m.dtype);
-  const sf_draft_weights &w = c->dw;
   Run r{c, (hipStream_t)stream};
   r.gemm_ws = ws + A.gemm_ws; r.gemm_ws_bytes = A.gemm_ws_bytes;
   // context rows: Grouped RMSNorm -> W_D -> K,V of the draft attention layer at the rows' positions
@@ -347,18 +367,45 @@ sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, 
   ra.kv_only = 1; ra.pos_mode = 1; ra.theta = m.rope_theta;
   LAUNCH(K_ROPE, launch_rope_table(ra, r.s));
   LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
-  // positional FFN on the newest committed row -> k slot states
-  norm(r, m, x, w.pos_norm, xl, B, 1, 2, qm, qm, st->n_new);
+  const void *norm_s = w.attn_norm, *wqkv_s = w.wqkv, *wo_s = w.wo;  // the slot attention's parameters
+  const void *kc_s = st->dk, *vc_s = st->dv;
+  const int32_t *len_s = st->kv_len;
+  int cap_s = cap, len_upper_s = len_upper;
+  if (!two_stage) {
+    // positional FFN on the newest committed row -> k slot states
+    norm(r, m, x, w.pos_norm, xl, B, 1, 2, qm, qm, st->n_new);
+  } else {
+    // The context attention's own output at the newest row (its K/V are in the cache by now):
+    // I_D = X + W_O . attention(RoPE(W_Q . RMS(X)), keys up to and including the row itself).
+    void *x_last = ws + A.x_last, *id_last = ws + A.id_last, *q1 = ws + A.q1, *qr1 = ws + A.qr1, *ao1 = ws + A.ao1;
+    int32_t *len_m1 = (int32_t *)(ws + A.len_m1);
+    LAUNCH(K_EMBED_HOOK, launch_gather_last(x, x_last, st->n_new, st->kv_len, len_m1, B, qm, d, m.dtype, r.s));
+    norm(r, m, x_last, w.attn_norm, a, B);
+    gemm(r, m.dtype, a, w.wqkv, nullptr, nullptr, q1, B, nq, d, 0);  // the nq query rows lead wqkv
+    RopeArgs rq{};
+    rq.qkv = q1; rq.q_out = qr1; rq.kc = nullptr; rq.vc = nullptr; rq.kv_len = len_m1; rq.n_new = nullptr;
+    rq.table = ra.table; rq.B = B; rq.n_q = 1; rq.Hq = m.n_q_heads; rq.Hkv = 0; rq.hd = m.head_dim; rq.cap = cap;
+    rq.kv_only = 0; rq.pos_mode = 0; rq.theta = m.rope_theta;
+    LAUNCH(K_ROPE, launch_rope_table(rq, r.s));
+    LAUNCH(K_ROPE, launch_rope_kv(rq, m.dtype, r.s));
+    attention(r, m, qr1, st->dk, st->dv, len_m1, ao1, part_o, part_ml, B, 1, cap, SF_MASK_CAUSAL, len_upper);
+    gemm(r, m.dtype, ao1, w.wo, nullptr, x_last, id_last, B, d, nq, 0);
+    norm(r, m, id_last, w.pos_norm, xl, B, 1, 3, 1, 1, st->n_new);
+    // the slots attend to each other only: an empty prefix in a one-tile cache of their own
+    norm_s = w.sa_norm; wqkv_s = w.sa_wqkv; wo_s = w.sa_wo;
+    kc_s = ws + A.kc2; vc_s = ws + A.vc2; len_s = (const int32_t *)(ws + A.zeros);
+    cap_s = TK; len_upper_s = 0;
+  }
   gemm(r, m.dtype, xl, w.w_pos, w.b_pos, nullptr, s0, B, k * d, d, 0);
   // one attention + SwiGLU layer over the slots
-  norm(r, m, s0, w.attn_norm, a, Ms);
-  gemm(r, m.dtype, a, w.wqkv, nullptr, nullptr, qkv, Ms, nq + 2 * nkv, d, 0);
-  ra.qkv = qkv; ra.q_out = qr; ra.n_new = nullptr; ra.n_q = k; ra.kv_only = 0; ra.pos_mode = 0;
+  norm(r, m, s0, norm_s, a, Ms);
+  gemm(r, m.dtype, a, wqkv_s, nullptr, nullptr, qkv, Ms, nq + 2 * nkv, d, 0);
+  ra.qkv = qkv; ra.q_out = qr; ra.kc = (void *)kc_s; ra.vc = (void *)vc_s; ra.kv_len = len_s; ra.n_new = nullptr;
+  ra.n_q = k; ra.cap = cap_s; ra.kv_only = 0; ra.pos_mode = 0;
   LAUNCH(K_ROPE, launch_rope_table(ra, r.s));
   LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
-  attention(r, m, qr, st->dk, st->dv, st->kv_len, ao, (float *)(ws + A.part_o), (float *)(ws + A.part_ml), B, k,
-            cap, mask, len_upper);
-  gemm(r, m.dtype, ao, w.wo, nullptr, s0, s0, Ms, d, nq, 0);
+  attention(r, m, qr, kc_s, vc_s, len_s, ao, part_o, part_ml, B, k, cap_s, mask, len_upper_s);
+  gemm(r, m.dtype, ao, wo_s, nullptr, s0, s0, Ms, d, nq, 0);
   norm(r, m, s0, w.ffn_norm, a, Ms);
   swiglu_in(r, m.dtype, a, w.w_gate_up, gu, act, Ms, F, d);
   gemm(r, m.dtype, act, w.w_down, nullptr, s0, s0, Ms, d, F, 0);

@@ -61,6 +61,8 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *__restrict__ X, c
     const int nn = n_new[r];
     zero = nn <= 0;
     in_row = (long)r * q + (zero ? 0 : min(nn, q) - 1);
+  } else if (map == 3) {  // row r itself, silenced when sequence r committed nothing
+    zero = n_new[r] <= 0;
   }
   const T *x = X + in_row * d;
   const T *gv = gain + (size_t)(r % n_gain) * d;
@@ -199,6 +201,19 @@ __global__ __launch_bounds__(256) void embed_kernel(const T *__restrict__ E, con
   for (int e = threadIdx.x; e < d; e += 256) { const T v = src[e]; h[e] = v; hk[e] = v; }
 }
 
+// The newest committed context row of every sequence, raw (the residual input of the context
+// attention's own output), and the number of keys that row sees before itself.
+template <typename T>
+__global__ __launch_bounds__(256) void gather_last_kernel(const T *__restrict__ X, T *__restrict__ out,
+                                                          const int32_t *__restrict__ n_new,
+                                                          const int32_t *__restrict__ kv_len,
+                                                          int32_t *__restrict__ len_m1, int q, int d) {
+  const int b = blockIdx.x, nn = n_new[b];
+  const T *src = X + ((size_t)b * q + (nn > 0 ? min(nn, q) - 1 : 0)) * d;
+  for (int e = threadIdx.x; e < d; e += 256) out[(size_t)b * d + e] = nn > 0 ? src[e] : T(0);
+  if (threadIdx.x == 0) len_m1[b] = max(kv_len[b] - 1, 0);
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void hook_copy_kernel(const T *__restrict__ H, T *__restrict__ hooks, int q,
                                                         int q_max, int d, int group) {
@@ -288,6 +303,15 @@ hipError_t launch_embed(const void *embed, const int32_t *pending, const int32_t
   else
     embed_kernel<float><<<M, 256, 0, s>>>((const float *)embed, pending, draft, (float *)h, (float *)hooks, k,
                                           q_max, d, vocab);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_last(const void *x, void *out, const int32_t *n_new, const int32_t *kv_len, int32_t *len_m1,
+                              int B, int q, int d, int dtype, hipStream_t s) {
+  if (dtype == SF_BF16)
+    gather_last_kernel<bf16_t><<<B, 256, 0, s>>>((const bf16_t *)x, (bf16_t *)out, n_new, kv_len, len_m1, q, d);
+  else
+    gather_last_kernel<float><<<B, 256, 0, s>>>((const float *)x, (float *)out, n_new, kv_len, len_m1, q, d);
   return hipGetLastError();
 }
 

@@ -121,6 +121,7 @@ struct NormArgs {
   float eps;
   // input row mapping: 0 identity; 1 hooks rows: r=(b*q+i)*4+g -> ((b*q_max+i)*4+g);
   // 2 newest committed row of x[B*q][d]: r=b -> b*q + n_new[b]-1 (zero row when n_new[b]==0)
+  // 3 identity, but a zero row when n_new[r]==0
   int map;
   int q, q_max;
   const int32_t *n_new;
@@ -147,6 +148,9 @@ hipError_t launch_rope_kv(const RopeArgs &a, int dtype, hipStream_t s);
 hipError_t launch_silu_mul(const float *gu, void *act, int M, int F, int dtype, hipStream_t s);
 hipError_t launch_embed(const void *embed, const int32_t *pending, const int32_t *draft, void *h, void *hooks,
                         int B, int k, int q_max, int d, int vocab, int dtype, hipStream_t s);
+// out[b] = x[b*q + n_new[b]-1] (zero row when n_new[b]==0); len_m1[b] = max(kv_len[b]-1, 0)
+hipError_t launch_gather_last(const void *x, void *out, const int32_t *n_new, const int32_t *kv_len, int32_t *len_m1,
+                              int B, int q, int d, int dtype, hipStream_t s);
 hipError_t launch_hook_copy(const void *h, void *hooks, int B, int q, int q_max, int d, int group, int dtype,
                             hipStream_t s);
 hipError_t launch_kv_convert(const void *src, void *dst, int is_v, int to_tiled, int B, int Hkv, int cap, int hd,

@@ -128,9 +128,11 @@ class Engine:
             D = sfb.DraftWeights()
             self.wd = {}
             for n, _ in sfb.DraftWeights._fields_:
+                if n.startswith("sa_") and n not in dw:        # two-stage wiring not used: NULL
+                    continue
                 if n == "w_gate_up":
                     self.wd[n] = gate_up(dw)
-                elif n in ("w_ds", "w_pos", "wqkv", "wo", "w_down"):
+                elif n in ("w_ds", "w_pos", "wqkv", "wo", "w_down", "sa_wqkv", "sa_wo"):
                     self.wd[n] = self._lin(dw[n])
                 else:
                     self.wd[n] = self._up(dw[n])

@@ -92,6 +92,20 @@ def test_steps_reject_bad_state_before_launching_anything():
     s.workspace = 0x10010
     assert L.sf_verify_step(ctx, C.byref(s), 4, fake, 0, fake, None) == sfb.SF_EINVAL      # misaligned
     assert L.sf_accept_commit(ctx, C.byref(s), 4, fake, None, None, fake, fake, None) == sfb.SF_EINVAL
+    # the slot attention's own weights come whole or not at all, and the two-stage wiring needs them
+    s.workspace = 0x10000
+    dw = sfb.DraftWeights()
+    for n, _ in sfb.DraftWeights._fields_:
+        setattr(dw, n, None if n.startswith("sa_") else fake)
+    assert L.sf_bind(ctx, C.byref(tw), C.byref(dw)) == sfb.SF_OK
+    two_stage = sfb.SF_MASK_BIDIR | sfb.SF_DRAFT_TWO_STAGE
+    assert L.sf_draft_step(ctx, C.byref(s), 4, two_stage, 0, fake, None, None) == sfb.SF_ESTATE
+    assert L.sf_draft_step(ctx, C.byref(s), 4, 7, 0, fake, None, None) == sfb.SF_EINVAL     # no such mask
+    dw.sa_norm = fake
+    assert L.sf_bind(ctx, C.byref(tw), C.byref(dw)) == sfb.SF_EINVAL
+    dw.pos_norm = None
+    dw.sa_norm = None
+    assert L.sf_bind(ctx, C.byref(tw), C.byref(dw)) == sfb.SF_EINVAL
     assert L.sf_last_hip_error(ctx) == 0
     assert b"capacity" in L.sf_strerror(sfb.SF_ECAPACITY)
     L.sf_destroy(ctx)
