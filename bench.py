@@ -38,31 +38,6 @@ def solve_alpha(kappa, k):
     return 0.5 * (lo + hi)
 
 
-def device_weights(m, k, seed, torch, two_stage=False):
-    """Random-init weights generated directly on the GPU (N(0, 0.02^2), norm gains 1)."""
-    g = torch.Generator(device="cuda")
-    g.manual_seed(seed)
-    dt = torch.bfloat16 if m.dtype == "bf16" else torch.float32
-
-    def rnd(*shape):
-        return (torch.randn(*shape, generator=g, device="cuda", dtype=torch.float32) * 0.02).to(dt)
-
-    def ones(*shape):
-        return torch.ones(*shape, device="cuda", dtype=dt)
-    d, hd, F, V, L = m.d_model, m.head_dim, m.d_ffn, m.vocab, m.n_layers
-    nqkv = (m.n_q_heads + 2 * m.n_kv_heads) * hd
-    tw = {"embed": rnd(V, d), "lm_head": rnd(V, d), "final_norm": ones(d),
-          "attn_norm": [ones(d) for _ in range(L)], "wqkv": [rnd(nqkv, d) for _ in range(L)],
-          "wo": [rnd(d, m.n_q_heads * hd) for _ in range(L)], "ffn_norm": [ones(d) for _ in range(L)],
-          "w_gate_up": [rnd(2 * F, d) for _ in range(L)], "w_down": [rnd(d, F) for _ in range(L)]}
-    dw = {"group_norm": ones(4, d), "w_ds": rnd(d, 4 * d), "pos_norm": ones(d), "w_pos": rnd(max(k, 1) * d, d),
-          "b_pos": rnd(max(k, 1) * d), "attn_norm": ones(d), "wqkv": rnd(nqkv, d), "wo": rnd(d, m.n_q_heads * hd),
-          "ffn_norm": ones(d), "w_gate_up": rnd(2 * F, d), "w_down": rnd(d, F), "out_norm": ones(d)}
-    if two_stage:      # the slot attention's own parameter set
-        dw.update({"sa_norm": ones(d), "sa_wqkv": rnd(nqkv, d), "sa_wo": rnd(d, m.n_q_heads * hd)})
-    return tw, dw
-
-
 def gemm_shapes(m, B, k, qm, two_stage=False):
     """(M, N, K, out_bytes_per_elem, has_residual) of every linear launch in one step."""
     es = 2 if m.dtype == "bf16" else 4
@@ -186,7 +161,7 @@ def main():
 
     import torch
     import synth
-    from paper_2511_20340_amd.engine import Engine
+    from paper_2511_20340_amd.engine import Engine, random_device_weights
     from paper_2511_20340_amd import binding as sfb
 
     wl = synth.WORKLOADS[args.config]
@@ -217,7 +192,7 @@ def main():
     two_stage = args.draft_wiring == "two-stage"
     draft_mode = (sfb.SF_MASK_BIDIR if args.draft_mask == "bidir" else sfb.SF_MASK_CAUSAL) | \
         (sfb.SF_DRAFT_TWO_STAGE if two_stage else 0)
-    tw, dw = device_weights(m, k, wl.seed, torch, two_stage)
+    tw, dw = random_device_weights(m, k, wl.seed, two_stage)
     eng.bind(tw, dw)
     del tw, dw
 

@@ -357,3 +357,30 @@ class Engine:
             if k > 0 and self._D is not None:
                 self.sf_draft_step(k)
         return self.pending.clone()
+
+
+def random_device_weights(m, k, seed, two_stage=False):
+    """Random-init weights of model shape m (synth.ModelShape) generated directly on the GPU:
+    N(0, 0.02^2) matrices, norm gains 1 -- the recipe of the benchmark workloads.  Returns the two
+    dicts Engine.bind takes."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    dt = torch.bfloat16 if m.dtype == "bf16" else torch.float32
+
+    def rnd(*shape):
+        return (torch.randn(*shape, generator=g, device="cuda", dtype=torch.float32) * 0.02).to(dt)
+
+    def ones(*shape):
+        return torch.ones(*shape, device="cuda", dtype=dt)
+    d, hd, F, V, L = m.d_model, m.head_dim, m.d_ffn, m.vocab, m.n_layers
+    nqkv = (m.n_q_heads + 2 * m.n_kv_heads) * hd
+    tw = {"embed": rnd(V, d), "lm_head": rnd(V, d), "final_norm": ones(d),
+          "attn_norm": [ones(d) for _ in range(L)], "wqkv": [rnd(nqkv, d) for _ in range(L)],
+          "wo": [rnd(d, m.n_q_heads * hd) for _ in range(L)], "ffn_norm": [ones(d) for _ in range(L)],
+          "w_gate_up": [rnd(2 * F, d) for _ in range(L)], "w_down": [rnd(d, F) for _ in range(L)]}
+    dw = {"group_norm": ones(4, d), "w_ds": rnd(d, 4 * d), "pos_norm": ones(d), "w_pos": rnd(max(k, 1) * d, d),
+          "b_pos": rnd(max(k, 1) * d), "attn_norm": ones(d), "wqkv": rnd(nqkv, d), "wo": rnd(d, m.n_q_heads * hd),
+          "ffn_norm": ones(d), "w_gate_up": rnd(2 * F, d), "w_down": rnd(d, F), "out_norm": ones(d)}
+    if two_stage:      # the slot attention's own parameter set
+        dw.update({"sa_norm": ones(d), "sa_wqkv": rnd(nqkv, d), "sa_wo": rnd(d, m.n_q_heads * hd)})
+    return tw, dw
