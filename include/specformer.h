@@ -77,10 +77,10 @@ typedef struct {
   const void *lm_head;            /* [vocab][d]  packed                            */
   const void *final_norm;         /* [d]                                           */
   const void *const *attn_norm;   /* L x [d]                                       */
-  const void *const *wqkv;        /* L x [(Hq+2Hkv)*hd][d]  rows: Q heads, K heads, V heads */
+  const void *const *wqkv;        /* L x [(Hq+2Hkv)*hd][d]  rows: Q heads, K heads, V heads; bf16: attn_norm folded */
   const void *const *wo;          /* L x [d][Hq*hd]                                */
   const void *const *ffn_norm;    /* L x [d]                                       */
-  const void *const *w_gate_up;   /* L x [2F][d]  rows [0,F) gate, [F,2F) up; packed with glu=1 */
+  const void *const *w_gate_up;   /* L x [2F][d]  rows [0,F) gate, [F,2F) up; packed with glu=1; bf16: ffn_norm folded */
   const void *const *w_down;      /* L x [d][F]                                    */
 } sf_target_weights;
 
@@ -92,15 +92,15 @@ typedef struct {
   const void *w_pos;      /* [k_max*d][d]  positional FFN W_P; slot s = rows [s*d,(s+1)*d)         */
   const void *b_pos;      /* [k_max*d]     positional FFN bias b_P                                 */
   const void *attn_norm;  /* [d]                                                                   */
-  const void *wqkv;       /* [(Hq+2Hkv)*hd][d]                                                     */
+  const void *wqkv;       /* [(Hq+2Hkv)*hd][d]  bf16: attn_norm folded                              */
   const void *wo;         /* [d][Hq*hd]                                                            */
   const void *ffn_norm;   /* [d]                                                                   */
-  const void *w_gate_up;  /* [2F][d]  packed with glu = 1                                          */
+  const void *w_gate_up;  /* [2F][d]  packed with glu = 1; bf16: ffn_norm folded                   */
   const void *w_down;     /* [d][F]                                                                */
   const void *out_norm;   /* [d]  the draft's own output norm; logits use the target's lm_head     */
   /* SF_DRAFT_TWO_STAGE only, NULL otherwise: the slot attention's own parameters                  */
   const void *sa_norm;    /* [d]                                                                   */
-  const void *sa_wqkv;    /* [(Hq+2Hkv)*hd][d]  packed                                             */
+  const void *sa_wqkv;    /* [(Hq+2Hkv)*hd][d]  packed; bf16: sa_norm folded                        */
   const void *sa_wo;      /* [d][Hq*hd]         packed                                             */
 } sf_draft_weights;
 
@@ -203,10 +203,15 @@ sf_status sf_op_attention(const sf_ctx *ctx, const void *q, const void *kc, cons
  * rows and columns zero-padded to multiples of 32 / 16; a prefix of whole 32-row blocks of a packed
  * matrix is itself a packed matrix (used for the K/V rows of wqkv and the first k slots of W_P).
  * glu != 0 (only for w_gate_up = [gate; up], N = 2F, F % 32 == 0): gate and up rows are interleaved 16 by
- * 16 so that the linear kernel's epilogue can form silu(gate)*up in registers. */
+ * 16 so that the linear kernel's epilogue can form silu(gate)*up in registers.
+ * col_gain (dev elem [K], or NULL): SF_BF16 only -- the gain vector of the RMSNorm whose output this
+ * layer consumes, folded into the weight's columns (w[n][k] * col_gain[k], rounded to bf16 once).  The
+ * decoder's norm + linear pairs run as ONE kernel on such weights (see sf_op_rmsnorm_linear), which is
+ * why, in SF_BF16 mode, the weight structs below want wqkv, w_gate_up and sa_wqkv packed with their
+ * norm's gains; SF_F32 mode ignores col_gain and applies the gains in its norm kernel. */
 size_t sf_packed_weight_bytes(const sf_ctx *ctx, int32_t N, int32_t K);
 sf_status sf_pack_weight(const sf_ctx *ctx, const void *w, void *packed, int32_t N, int32_t K, int32_t glu,
-                         void *stream);
+                         const void *col_gain, void *stream);
 
 /* y[M][N] = x[M][K] . w[N][K]^T (+ bias[N]) (+ residual[M][N]); x, bias, residual: dev elem; w: packed;
  * fp32 accumulation; y: dev elem, or float when out_f32 != 0.  K % 8 == 0, N % 8 == 0.
@@ -218,6 +223,15 @@ size_t sf_linear_workspace_bytes(const sf_ctx *ctx, int32_t M);
 sf_status sf_op_linear(const sf_ctx *ctx, const void *x, const void *w, const void *bias,
                        const void *residual, void *y, int32_t M, int32_t N, int32_t K, int32_t out_f32,
                        void *workspace, size_t workspace_bytes, void *stream);
+/* Fused y = RMSNorm(x; gain, eps of the target configuration) . w^T, SF_BF16 only (SF_EUNSUPPORTED
+ * otherwise): what the decoder layers run in place of a norm kernel followed by a linear kernel.  w must
+ * have been packed with col_gain = gain; the kernel streams the raw x, accumulates every row's sum of
+ * squares on the way, and scales its fp32 accumulators by the row factor 1/sqrt(mean(x^2)+eps), which
+ * commutes with the K sum; the normalised activations never reach HBM.  x: dev bf16 [M][K]; other
+ * arguments as sf_op_linear. */
+sf_status sf_op_rmsnorm_linear(const sf_ctx *ctx, const void *x, const void *w, void *y, int32_t M, int32_t N,
+                               int32_t K, int32_t out_f32, void *workspace, size_t workspace_bytes,
+                               void *stream);
 /* SwiGLU input half: act[M][F] = silu(x . Wg^T) * (x . Wu^T); w_gate_up packed with glu = 1 (SF_BF16:
  * one kernel, gate/up never leave registers; SF_F32: workspace must hold M*2F floats). act: dev elem. */
 sf_status sf_op_linear_swiglu(const sf_ctx *ctx, const void *x, const void *w_gate_up, void *act, int32_t M,

@@ -29,8 +29,34 @@ static void round_buf(double *x, long n, int on) {
   for (long i = 0; i < n; ++i) x[i] = sfo_round_bf16(x[i]);
 }
 
-/* RMS normalisation, Context Causal Attention paragraph ("RMS Norm"):
- * y = g * x / sqrt(mean(x^2) + eps), statistics over the last dimension. */
+/* y = RMSNorm(x; g) . w^T for the norm + linear pairs of the decoder layers.  Exact mode: the two
+ * definitions one after the other.  bf16 emulation: the path under test stores neither the normalised
+ * rows nor the gains separately -- the gain vector is folded into the weight's columns once (rounded
+ * to bf16), the matrix product runs on the raw rows, and the row factor 1/sqrt(mean(x^2)+eps), which
+ * commutes with the sum over the features, is applied unrounded -- so the emulation rounds w*g and
+ * nothing else. */
+static void norm_linear(const double *x, const float *g, const float *w, int M, int K, int N, double eps, int on,
+                        double *y) {
+  if (!on) {
+    double *a = (double *)malloc(sizeof(double) * (size_t)M * K);
+    sfo_rmsnorm(x, g, M, K, eps, a);
+    sfo_linear(a, w, NULL, M, K, N, y);
+    free(a);
+    return;
+  }
+  float *wf = (float *)malloc(sizeof(float) * (size_t)N * K);
+  for (long n = 0; n < N; ++n)
+    for (int k = 0; k < K; ++k) wf[n * K + k] = (float)sfo_round_bf16((double)w[n * K + k] * (double)g[k]);
+  sfo_linear(x, wf, NULL, M, K, N, y);
+  free(wf);
+  for (int r = 0; r < M; ++r) {
+    double ss = 0.0;
+    for (int e = 0; e < K; ++e) ss += x[(long)r * K + e] * x[(long)r * K + e];
+    double rinv = 1.0 / sqrt(ss / K + eps);
+    for (int n = 0; n < N; ++n) y[(long)r * N + n] *= rinv;
+  }
+}
+
 void sfo_rmsnorm(const double *x, const float *g, int M, int d, double eps, double *y) {
   for (int r = 0; r < M; ++r) {
     const double *xr = x + (long)r * d;
@@ -161,9 +187,7 @@ static void attn_half(const sfo_cfg *c, const float *norm_g, const float *wqkv, 
   double *q = dalloc((long)M * NQ), *kk = dalloc((long)M * NKV), *o = dalloc((long)M * NQ);
   double *proj = dalloc((long)M * d);
   int32_t *pos = (int32_t *)malloc(sizeof(int32_t) * (size_t)M);
-  sfo_rmsnorm(h, norm_g, M, d, c->rms_eps, a);
-  round_buf(a, (long)M * d, R);
-  sfo_linear(a, wqkv, NULL, M, d, N, qkv);
+  norm_linear(h, norm_g, wqkv, M, d, N, c->rms_eps, R, qkv);
   round_buf(qkv, (long)M * N, R);
   for (int b = 0; b < B; ++b)
     for (int i = 0; i < nq; ++i) pos[b * nq + i] = len[b] + i;
@@ -198,10 +222,8 @@ static void ffn_half(const sfo_cfg *c, const float *norm_g, const float *wg, con
   int d = c->d_model, F = c->d_ffn, R = c->round_bf16;
   double *a = dalloc((long)M * d), *g = dalloc((long)M * F), *u = dalloc((long)M * F);
   double *proj = dalloc((long)M * d);
-  sfo_rmsnorm(h, norm_g, M, d, c->rms_eps, a);
-  round_buf(a, (long)M * d, R);
-  sfo_linear(a, wg, NULL, M, d, F, g);
-  sfo_linear(a, wu, NULL, M, d, F, u);
+  norm_linear(h, norm_g, wg, M, d, F, c->rms_eps, R, g);
+  norm_linear(h, norm_g, wu, M, d, F, c->rms_eps, R, u);
   sfo_silu_mul(g, u, (long)M * F, g);
   round_buf(g, (long)M * F, R);
   sfo_linear(g, wd, NULL, M, F, d, proj);
@@ -295,9 +317,7 @@ int sfo_draft_step(const sfo_cfg *c, const sfo_draft_weights *w, const float *lm
     round_buf(f, (long)n * 4 * d, R);
     sfo_linear(f, w->w_ds, NULL, n, 4 * d, d, x);
     round_buf(x, (long)n * d, R);
-    sfo_rmsnorm(x, w->attn_norm, n, d, c->rms_eps, a);
-    round_buf(a, (long)n * d, R);
-    sfo_linear(a, w->wqkv, NULL, n, d, N, qkv);
+    norm_linear(x, w->attn_norm, w->wqkv, n, d, N, c->rms_eps, R, qkv);
     round_buf(qkv, (long)n * N, R);
     for (int r = 0; r < n; ++r) {
       pos[r] = s->kv_len[b] - n + r;

@@ -15,7 +15,7 @@ KERNEL_CLASSES = ["linear", "attention", "attention_combine", "rmsnorm", "rope_k
 EXPORTS = [
     "sf_create", "sf_destroy", "sf_workspace_bytes", "sf_kv_cache_bytes", "sf_bind", "sf_draft_step",
     "sf_verify_step", "sf_accept_commit", "sf_kv_import", "sf_kv_export", "sf_attention_workspace_bytes",
-    "sf_op_attention", "sf_packed_weight_bytes", "sf_pack_weight", "sf_linear_workspace_bytes", "sf_op_linear", "sf_op_linear_swiglu", "sf_tune_linear", "sf_linear_num_tiles", "sf_linear_config", "sf_tune_attention", "sf_op_rmsnorm", "sf_op_rope_kv_append", "sf_op_silu_mul",
+    "sf_op_attention", "sf_packed_weight_bytes", "sf_pack_weight", "sf_linear_workspace_bytes", "sf_op_linear", "sf_op_rmsnorm_linear", "sf_op_linear_swiglu", "sf_tune_linear", "sf_linear_num_tiles", "sf_linear_config", "sf_tune_attention", "sf_op_rmsnorm", "sf_op_rope_kv_append", "sf_op_silu_mul",
     "sf_argmax_workspace_bytes", "sf_op_argmax", "sf_calib_copy", "sf_profile_begin", "sf_profile_end", "sf_strerror", "sf_last_hip_error", "sf_version",
 ]
 
@@ -83,9 +83,10 @@ def lib():
     L.sf_attention_workspace_bytes.restype = sz
     L.sf_op_attention.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
     L.sf_op_linear.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]
+    L.sf_op_rmsnorm_linear.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]
     L.sf_packed_weight_bytes.argtypes = [vp, i32, i32]
     L.sf_packed_weight_bytes.restype = sz
-    L.sf_pack_weight.argtypes = [vp, vp, vp, i32, i32, i32, vp]
+    L.sf_pack_weight.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
     L.sf_op_linear_swiglu.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, sz, vp]
     L.sf_linear_workspace_bytes.argtypes = [vp, i32]
     L.sf_linear_workspace_bytes.restype = sz

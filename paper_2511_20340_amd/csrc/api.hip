@@ -147,18 +147,20 @@ struct Run {
 #define LAUNCH(cls, expr) r.launch(cls, [&] { return (expr); })
 
 void gemm(Run &r, int dtype, const void *x, const void *w, const void *bias, const void *res, void *y, int M, int N,
-          int K, int out_f32, int glu = 0) {
+          int K, int out_f32, int glu = 0, int fused_norm = 0, float norm_eps = 0.f) {
   if (r.st != SF_OK) return;
   GemmArgs g{x, w, bias, res, y, M, N, K, out_f32, glu, r.gemm_ws, r.gemm_ws_bytes};
   g.plan_M = r.plan_rows;
+  g.fused_norm = fused_norm; g.norm_eps = norm_eps;
   LAUNCH(K_GEMM, dtype == SF_BF16 ? launch_gemm_bf16(g, r.s) : launch_gemm_f32(g, r.s));
 }
 
 // act[M][F] = silu(a . Wg^T) * (a . Wu^T): one kernel in bf16 mode (weight packed with glu = 1), GEMM to
 // fp32 + gating kernel in fp32 mode
-void swiglu_in(Run &r, int dtype, const void *a, const void *w_gate_up, float *gu, void *act, int M, int F, int K) {
+void swiglu_in(Run &r, int dtype, const void *a, const void *w_gate_up, float *gu, void *act, int M, int F, int K,
+               int fused_norm = 0, float norm_eps = 0.f) {
   if (dtype == SF_BF16) {
-    gemm(r, dtype, a, w_gate_up, nullptr, nullptr, act, M, 2 * F, K, 0, 1);
+    gemm(r, dtype, a, w_gate_up, nullptr, nullptr, act, M, 2 * F, K, 0, 1, fused_norm, norm_eps);
   } else {
     gemm(r, dtype, a, w_gate_up, nullptr, nullptr, gu, M, 2 * F, K, 1);
     LAUNCH(K_SILU, launch_silu_mul(gu, act, M, F, dtype, r.s));
@@ -170,6 +172,29 @@ void norm(Run &r, const sf_model_cfg &m, const void *x, const void *gain, void *
   if (r.st != SF_OK) return;
   NormArgs n{x, gain, y, M, m.d_model, n_gain, m.rms_eps, map, q, q_max, n_new};
   LAUNCH(K_NORM, launch_rmsnorm(n, m.dtype, r.s));
+}
+
+// y = RMSNorm(x; gain) . w^T.  bf16: ONE kernel -- w was packed with the gain folded into its columns,
+// the linear kernel takes the raw rows, sums their squares while staging them and scales its
+// accumulators by the row factor.  fp32: the norm kernel into `tmp`, then the linear kernel.
+void norm_gemm(Run &r, const sf_model_cfg &m, const void *x, const void *gain, void *tmp, const void *w, void *y,
+               int M, int N, int K, int out_f32) {
+  if (m.dtype == SF_BF16) {
+    gemm(r, m.dtype, x, w, nullptr, nullptr, y, M, N, K, out_f32, 0, 1, m.rms_eps);
+  } else {
+    norm(r, m, x, gain, tmp, M);
+    gemm(r, m.dtype, tmp, w, nullptr, nullptr, y, M, N, K, out_f32);
+  }
+}
+
+void norm_swiglu_in(Run &r, const sf_model_cfg &m, const void *x, const void *gain, void *tmp, const void *w_gate_up,
+                    float *gu, void *act, int M, int F, int K) {
+  if (m.dtype == SF_BF16) {
+    swiglu_in(r, m.dtype, x, w_gate_up, gu, act, M, F, K, 1, m.rms_eps);
+  } else {
+    norm(r, m, x, gain, tmp, M);
+    swiglu_in(r, m.dtype, tmp, w_gate_up, gu, act, M, F, K);
+  }
 }
 
 void attention(Run &r, const sf_model_cfg &m, const void *q, const void *kc, const void *vc, const int32_t *kv_len,
@@ -311,17 +336,16 @@ sf_status sf_verify_step(sf_ctx *c, const sf_state *st, int32_t k, const int32_t
       if (hook_layer[g] == l) LAUNCH(K_EMBED_HOOK, launch_hook_copy(h, st->hooks, B, q, qm, d, g, m.dtype, r.s));
     if (l == L) break;
     void *kc = (char *)st->tk + l * lb, *vc = (char *)st->tv + l * lb;
-    norm(r, m, h, c->attn_norm[l], a, M);
-    gemm(r, m.dtype, a, c->wqkv[l], nullptr, nullptr, qkv, M, nq + 2 * nkv, d, 0);
+    norm_gemm(r, m, h, c->attn_norm[l], a, c->wqkv[l], qkv, M, nq + 2 * nkv, d, 0);
     ra.kc = kc; ra.vc = vc;
     LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
     attention(r, m, qr, kc, vc, st->kv_len, ao, (float *)(ws + A.part_o), (float *)(ws + A.part_ml), B, q, cap,
               SF_MASK_CAUSAL, len_upper);
     gemm(r, m.dtype, ao, c->wo[l], nullptr, h, h, M, d, nq, 0);
-    norm(r, m, h, c->ffn_norm[l], a, M);
-    swiglu_in(r, m.dtype, a, c->w_gate_up[l], gu, act, M, F, d);
+    norm_swiglu_in(r, m, h, c->ffn_norm[l], a, c->w_gate_up[l], gu, act, M, F, d);
     gemm(r, m.dtype, act, c->w_down[l], nullptr, h, h, M, d, F, 0);
   }
+  // the LM head serves two norms (this one and the draft's), so no gain is folded into it
   norm(r, m, h, c->tw.final_norm, a, M);
   gemm(r, m.dtype, a, c->tw.lm_head, nullptr, nullptr, logits, M, m.vocab, d, 1);
   return r.st;
@@ -356,10 +380,9 @@ sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, 
   // context rows: Grouped RMSNorm -> W_D -> K,V of the draft attention layer at the rows' positions
   norm(r, m, st->hooks, w.group_norm, f4, Mh * 4, 4, 1, qm, qm, nullptr);
   gemm(r, m.dtype, f4, w.w_ds, nullptr, nullptr, x, Mh, d, 4 * d, 0);
-  norm(r, m, x, w.attn_norm, a, Mh);
   // K and V rows of wqkv start after the nq query rows (a whole number of packed 32-row blocks)
   const size_t kv_off = m.dtype == SF_BF16 ? packed_weight_bytes(nq, d, m.dtype) : (size_t)nq * d * es;
-  gemm(r, m.dtype, a, (const char *)w.wqkv + kv_off, nullptr, nullptr, kvc, Mh, 2 * nkv, d, 0);
+  norm_gemm(r, m, x, w.attn_norm, a, (const char *)w.wqkv + kv_off, kvc, Mh, 2 * nkv, d, 0);
   RopeArgs ra{};
   ra.qkv = kvc; ra.q_out = nullptr; ra.kc = st->dk; ra.vc = st->dv; ra.kv_len = st->kv_len; ra.n_new = st->n_new;
   ra.table = (float2 *)(ws + A.table);
@@ -380,8 +403,7 @@ sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, 
     void *x_last = ws + A.x_last, *id_last = ws + A.id_last, *q1 = ws + A.q1, *qr1 = ws + A.qr1, *ao1 = ws + A.ao1;
     int32_t *len_m1 = (int32_t *)(ws + A.len_m1);
     LAUNCH(K_EMBED_HOOK, launch_gather_last(x, x_last, st->n_new, st->kv_len, len_m1, B, qm, d, m.dtype, r.s));
-    norm(r, m, x_last, w.attn_norm, a, B);
-    gemm(r, m.dtype, a, w.wqkv, nullptr, nullptr, q1, B, nq, d, 0);  // the nq query rows lead wqkv
+    norm_gemm(r, m, x_last, w.attn_norm, a, w.wqkv, q1, B, nq, d, 0);  // the nq query rows lead wqkv
     RopeArgs rq{};
     rq.qkv = q1; rq.q_out = qr1; rq.kc = nullptr; rq.vc = nullptr; rq.kv_len = len_m1; rq.n_new = nullptr;
     rq.table = ra.table; rq.B = B; rq.n_q = 1; rq.Hq = m.n_q_heads; rq.Hkv = 0; rq.hd = m.head_dim; rq.cap = cap;
@@ -398,16 +420,14 @@ sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, 
   }
   gemm(r, m.dtype, xl, w.w_pos, w.b_pos, nullptr, s0, B, k * d, d, 0);
   // one attention + SwiGLU layer over the slots
-  norm(r, m, s0, norm_s, a, Ms);
-  gemm(r, m.dtype, a, wqkv_s, nullptr, nullptr, qkv, Ms, nq + 2 * nkv, d, 0);
+  norm_gemm(r, m, s0, norm_s, a, wqkv_s, qkv, Ms, nq + 2 * nkv, d, 0);
   ra.qkv = qkv; ra.q_out = qr; ra.kc = (void *)kc_s; ra.vc = (void *)vc_s; ra.kv_len = len_s; ra.n_new = nullptr;
   ra.n_q = k; ra.cap = cap_s; ra.kv_only = 0; ra.pos_mode = 0;
   LAUNCH(K_ROPE, launch_rope_table(ra, r.s));
   LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
   attention(r, m, qr, kc_s, vc_s, len_s, ao, part_o, part_ml, B, k, cap_s, mask, len_upper_s);
   gemm(r, m.dtype, ao, wo_s, nullptr, s0, s0, Ms, d, nq, 0);
-  norm(r, m, s0, w.ffn_norm, a, Ms);
-  swiglu_in(r, m.dtype, a, w.w_gate_up, gu, act, Ms, F, d);
+  norm_swiglu_in(r, m, s0, w.ffn_norm, a, w.w_gate_up, gu, act, Ms, F, d);
   gemm(r, m.dtype, act, w.w_down, nullptr, s0, s0, Ms, d, F, 0);
   norm(r, m, s0, w.out_norm, a, Ms);
   gemm(r, m.dtype, a, c->tw.lm_head, nullptr, nullptr, dlogits, Ms, m.vocab, d, 1);
@@ -481,11 +501,12 @@ size_t sf_packed_weight_bytes(const sf_ctx *c, int32_t N, int32_t K) {
 }
 
 sf_status sf_pack_weight(const sf_ctx *c, const void *w, void *packed, int32_t N, int32_t K, int32_t glu,
-                         void *stream) {
+                         const void *col_gain, void *stream) {
   if (!c || !w || !packed || N < 1 || K < 1) return SF_EINVAL;
   if (((uintptr_t)packed) % 16) return SF_EINVAL;
   if (glu && (N % 64)) return SF_EUNSUPPORTED;  // F = N/2 must be a multiple of 32
-  hipError_t e = launch_pack_weight(w, packed, N, K, glu, c->tc.dtype, (hipStream_t)stream);
+  hipError_t e = launch_pack_weight(w, packed, N, K, glu, c->tc.dtype == SF_BF16 ? col_gain : nullptr, c->tc.dtype,
+                                    (hipStream_t)stream);
   if (e != hipSuccess) { c->hip_err = (int)e; return SF_EHIP; }
   return SF_OK;
 }
@@ -527,6 +548,18 @@ sf_status sf_op_linear(const sf_ctx *c, const void *x, const void *w, const void
   Run r{c, (hipStream_t)stream};
   r.gemm_ws = workspace; r.gemm_ws_bytes = workspace ? workspace_bytes : 0;
   gemm(r, c->tc.dtype, x, w, bias, residual, y, M, N, K, out_f32);
+  return r.st;
+}
+
+sf_status sf_op_rmsnorm_linear(const sf_ctx *c, const void *x, const void *w, void *y, int32_t M, int32_t N,
+                               int32_t K, int32_t out_f32, void *workspace, size_t workspace_bytes, void *stream) {
+  if (!c || !x || !w || !y || M < 1 || N < 1 || K < 1) return SF_EINVAL;
+  if (c->tc.dtype != SF_BF16 || K % 8 || N % 8) return SF_EUNSUPPORTED;
+  if (((uintptr_t)x | (uintptr_t)w) % 16) return SF_EINVAL;
+  if (workspace && ((uintptr_t)workspace) % ALIGN) return SF_EINVAL;
+  Run r{c, (hipStream_t)stream};
+  r.gemm_ws = workspace; r.gemm_ws_bytes = workspace ? workspace_bytes : 0;
+  gemm(r, SF_BF16, x, w, nullptr, nullptr, y, M, N, K, out_f32, 0, 1, c->tc.rms_eps);
   return r.st;
 }
 

@@ -37,12 +37,20 @@ constexpr int XCDS = 8;
 
 // What every bf16 kernel variant does once a workgroup holds its accumulators: the split-K hand-over
 // (partials, ticket, ordered sum in the last workgroup to arrive) and the output epilogue.
+//
+// Fused RMSNorm (sS != nullptr): the weight was packed with the norm's gain vector folded into its
+// columns, the main loop ran on the raw activations and left each row's sum of squares over this
+// workgroup's K range in sS[BM]; the row factor 1/sqrt(mean(x^2)+eps) commutes with the K sum and
+// is applied to the accumulators here.  With split-K the per-split sums travel next to the partial
+// tiles and are added in split order too.
 template <int TM, int TN, int NW = 4>
 __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const bf16_t *__restrict__ bias,
                                             const bf16_t *residual, void *Y, int M, int N, int out_f32, int tiles_m,
                                             int split_k, float *__restrict__ partial,
                                             unsigned *__restrict__ tickets, int glu, int tm, int tn, int ks, int m0,
-                                            int nb0, unsigned &s_ticket) {
+                                            int nb0, unsigned &s_ticket, float *sS = nullptr,
+                                            float *__restrict__ ssq_part = nullptr, int K = 1, float eps = 0.f) {
+  constexpr int BM = TM * 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
   if (split_k > 1) {
@@ -60,6 +68,9 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const bf16_t 
         for (int v = 0; v < 16; ++v)
           __hip_atomic_store(mine + ((a * TN + b) * 16 + v) * 64 + lane, acc[a][b][v], __ATOMIC_RELAXED,
                              __HIP_MEMORY_SCOPE_AGENT);
+    if (sS && tid < BM)
+      __hip_atomic_store(ssq_part + (tile * split_k + ks) * BM + tid, sS[tid], __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's stores have been acknowledged
     __syncthreads();
     if (tid == 0) s_ticket = __hip_atomic_fetch_add(&tickets[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -82,7 +93,30 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const bf16_t 
             acc[a][b][v] += __hip_atomic_load(p + ((a * TN + b) * 16 + v) * 64 + lane, __ATOMIC_RELAXED,
                                               __HIP_MEMORY_SCOPE_AGENT);
     }
+    if (sS) {
+      if (tid < BM) {
+        float t = 0.f;
+        for (int s = 0; s < split_k; ++s)
+          t += __hip_atomic_load(ssq_part + (tile * split_k + s) * BM + tid, __ATOMIC_RELAXED,
+                                 __HIP_MEMORY_SCOPE_AGENT);
+        sS[tid] = t;
+      }
+      __syncthreads();
+    }
     if (tid == 0) __hip_atomic_store(&tickets[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+
+  if (sS) {
+    if (tid < BM) sS[tid] = 1.0f / sqrtf(sS[tid] / (float)K + eps);  // one row factor per row, once
+    __syncthreads();
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float rinv = sS[a * 32 + c_row(v, lh)];
+#pragma unroll
+        for (int b = 0; b < TN; ++b) acc[a][b][v] *= rinv;
+      }
   }
 
   if (glu) {
@@ -143,20 +177,22 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const bf16_t 
 // The bf16 kernel.  TM 32-row activation blocks x TN weight row blocks per wave, NW waves, ring
 // depth R.  Slot indices are compile-time after unrolling by R; the loop runs whole rounds of R
 // slices, and slices past the workgroup's K range contribute zeros.
-template <int TM, int TN, int R, int OCC, int NW>
+template <int TM, int TN, int R, int OCC, int NW, int NORM>
 __global__ __launch_bounds__(64 * NW, OCC) void gemm_ring_kernel(const bf16_t *__restrict__ A,
                                                         const uint4 *__restrict__ Wp,
                                                         const bf16_t *__restrict__ bias, const bf16_t *residual,
                                                         void *Y, int M, int N, int K, int out_f32, int tiles_m,
                                                         int tiles_n, int split_k, int kt_per_split,
                                                         float *__restrict__ partial,
-                                                        unsigned *__restrict__ tickets, int glu) {
+                                                        unsigned *__restrict__ tickets, int glu, float eps,
+                                                        float *__restrict__ ssq_part) {
   static_assert(R >= 2, "the slot after the current one holds the next activation chunk");
   constexpr int BM = TM * 32;
   constexpr int NT = 64 * NW;              // threads
   constexpr int CH = TM * 256;             // 16-byte activation chunks per K slice
   constexpr int CPT = (CH + NT - 1) / NT;  // chunks per thread
-  extern __shared__ __attribute__((aligned(16))) bf16_t sA[];  // [2][BM][LDK]
+  // [2][BM][LDK] activations; NORM: then float sS[BM], the rows' sums of squares
+  extern __shared__ __attribute__((aligned(16))) bf16_t sA[];
   __shared__ unsigned s_ticket;
 
   const int id = blockIdx.x;
@@ -173,6 +209,10 @@ __global__ __launch_bounds__(64 * NW, OCC) void gemm_ring_kernel(const bf16_t *_
   const int nb0 = (tn * NW + wave) * TN;
   const int KT = (K + BK - 1) / BK;
   const int kt0 = ks * kt_per_split, kt1 = min(KT, kt0 + kt_per_split);
+  float *sS = reinterpret_cast<float *>(sA + 2 * BM * LDK);
+  float ssq[CPT];
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) ssq[c] = 0.f;
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -205,6 +245,14 @@ __global__ __launch_bounds__(64 * NW, OCC) void gemm_ring_kernel(const bf16_t *_
       const bool live = kt < kt1 && kt * BK + kc < K;
       uint4 v = r[c];
       v.x = live ? v.x : 0u; v.y = live ? v.y : 0u; v.z = live ? v.z : 0u; v.w = live ? v.w : 0u;
+      if (NORM) {  // the row's sum of squares, two bf16 products per instruction
+        float t = ssq[c];
+        t = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, v.x), __builtin_bit_cast(bf16x2, v.x), t, false);
+        t = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, v.y), __builtin_bit_cast(bf16x2, v.y), t, false);
+        t = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, v.z), __builtin_bit_cast(bf16x2, v.z), t, false);
+        t = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, v.w), __builtin_bit_cast(bf16x2, v.w), t, false);
+        ssq[c] = t;
+      }
       *reinterpret_cast<uint4 *>(sA + (buf * BM + row) * LDK + kc) = v;
     }
   };
@@ -248,15 +296,30 @@ __global__ __launch_bounds__(64 * NW, OCC) void gemm_ring_kernel(const bf16_t *_
       __syncthreads();
     }
   }
+  if (NORM) {
+    // the 8 threads that carried a row's chunks sit in adjacent lanes
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      float t = ssq[c];
+      t += __shfl_xor(t, 1);
+      t += __shfl_xor(t, 2);
+      t += __shfl_xor(t, 4);
+      const int cid = tid + NT * c;
+      if ((tid & 7) == 0 && cid < CH) sS[cid >> 3] = t;
+    }
+    __syncthreads();
+  }
   gemm_finish<TM, TN, NW>(acc, bias, residual, Y, M, N, out_f32, tiles_m, split_k, partial, tickets, glu, tm, tn, ks, m0, nb0,
-                      s_ticket);
+                      s_ticket, NORM ? sS : nullptr, ssq_part, K, eps);
 }
 
 // row-major [N][K] -> packed units; one thread per 16-byte operand register
 // glu_F > 0: W is [2F][K] = [gate; up] and packed row block nb holds gate rows 16nb..16nb+15 followed
 // by up rows 16nb..16nb+15 (see the SwiGLU epilogue)
+// col_gain != nullptr: column k of W is multiplied by col_gain[k] (rounded to bf16 again): the gain
+// vector of the RMSNorm in front of this layer, folded in for the fused norm
 __global__ void pack_weight_kernel(const bf16_t *__restrict__ W, uint4 *__restrict__ P, int N, int K, size_t units,
-                                   int glu_F) {
+                                   int glu_F, const bf16_t *__restrict__ col_gain) {
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= units) return;
   const int lane = idx & 63;
@@ -273,7 +336,11 @@ __global__ void pack_weight_kernel(const bf16_t *__restrict__ W, uint4 *__restri
   uint32_t w[4] = {0, 0, 0, 0};
   if (row < N)
     for (int e = 0; e < 8; ++e)
-      if (k0 + e < K) w[e >> 1] |= (uint32_t)W[(size_t)row * K + k0 + e] << ((e & 1) * 16);
+      if (k0 + e < K) {
+        bf16_t v = W[(size_t)row * K + k0 + e];
+        if (col_gain) v = f2bf(bf2f(v) * bf2f(col_gain[k0 + e]));
+        w[e >> 1] |= (uint32_t)v << ((e & 1) * 16);
+      }
   P[idx] = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
@@ -298,9 +365,12 @@ Plan make_plan(int M, int N, int K, int BM, int BN, int split) {
   return p;
 }
 
-bool plan_fits(const Plan &p, const void *ws, size_t ws_bytes) {
-  return p.split_k == 1 ||
-         (ws && ws_bytes >= GEMM_TICKET_BYTES + p.partial_bytes && p.ticket_bytes <= GEMM_TICKET_BYTES);
+// workspace: [tickets][row sums of squares of the fused norm][partial tiles]
+bool plan_fits(const Plan &p, int BM, const void *ws, size_t ws_bytes) {
+  if (p.split_k == 1) return true;
+  const size_t ssq_bytes = (size_t)p.tiles_m * p.tiles_n * p.split_k * BM * sizeof(float);
+  return ws && ws_bytes >= GEMM_TICKET_BYTES + GEMM_SSQ_BYTES + p.partial_bytes &&
+         p.ticket_bytes <= GEMM_TICKET_BYTES && ssq_bytes <= GEMM_SSQ_BYTES;
 }
 
 // mode 0: launch; mode 1: only report whether (split) fits the workspace
@@ -308,15 +378,25 @@ template <int TM, int TN, int R, int OCC, int NW>
 hipError_t run_ring(const GemmArgs &a, hipStream_t s, int split, int mode) {
   constexpr int BM = TM * 32, BN = NW * TN * 32;
   const Plan p = make_plan(a.M, a.N, a.K, BM, BN, split);
-  if (!plan_fits(p, a.ws, a.ws_bytes)) return hipErrorInvalidValue;
+  if (!plan_fits(p, BM, a.ws, a.ws_bytes)) return hipErrorInvalidValue;
   if (mode == 1) return hipSuccess;
   const int groups = (p.tiles_n + XCDS - 1) / XCDS;
-  const size_t lds = (size_t)2 * BM * LDK * sizeof(bf16_t);
+  size_t lds = (size_t)2 * BM * LDK * sizeof(bf16_t);
   unsigned *tickets = (unsigned *)a.ws;
-  float *partial = a.ws ? (float *)((char *)a.ws + GEMM_TICKET_BYTES) : nullptr;
-  gemm_ring_kernel<TM, TN, R, OCC, NW><<<dim3(groups * XCDS * p.tiles_m * p.split_k), dim3(64 * NW), lds, s>>>(
-      (const bf16_t *)a.x, (const uint4 *)a.w, (const bf16_t *)a.bias, (const bf16_t *)a.residual, a.y, a.M, a.N,
-      a.K, a.out_f32, p.tiles_m, p.tiles_n, p.split_k, p.kt_per_split, partial, tickets, a.glu);
+  float *ssq_part = a.ws ? (float *)((char *)a.ws + GEMM_TICKET_BYTES) : nullptr;
+  float *partial = a.ws ? (float *)((char *)a.ws + GEMM_TICKET_BYTES + GEMM_SSQ_BYTES) : nullptr;
+  const dim3 grid(groups * XCDS * p.tiles_m * p.split_k), block(64 * NW);
+  if (a.fused_norm) {
+    lds += (size_t)BM * sizeof(float);
+    gemm_ring_kernel<TM, TN, R, OCC, NW, 1><<<grid, block, lds, s>>>(
+        (const bf16_t *)a.x, (const uint4 *)a.w, (const bf16_t *)a.bias, (const bf16_t *)a.residual, a.y, a.M, a.N,
+        a.K, a.out_f32, p.tiles_m, p.tiles_n, p.split_k, p.kt_per_split, partial, tickets, a.glu, a.norm_eps,
+        ssq_part);
+  } else {
+    gemm_ring_kernel<TM, TN, R, OCC, NW, 0><<<grid, block, lds, s>>>(
+        (const bf16_t *)a.x, (const uint4 *)a.w, (const bf16_t *)a.bias, (const bf16_t *)a.residual, a.y, a.M, a.N,
+        a.K, a.out_f32, p.tiles_m, p.tiles_n, p.split_k, p.kt_per_split, partial, tickets, a.glu, 0.f, nullptr);
+  }
   return hipGetLastError();
 }
 
@@ -366,7 +446,7 @@ GemmConfig pick(int M, int N, int K, size_t ws_bytes, int fixed_split) {
   auto fits = [&](int tm, int split) {
     if (split == 1) return true;
     const Plan p = make_plan(M, N, K, tm * 32, 128, split);
-    return ws_bytes >= GEMM_TICKET_BYTES + p.partial_bytes && p.ticket_bytes <= GEMM_TICKET_BYTES;
+    return plan_fits(p, tm * 32, (const void *)1, ws_bytes);
   };
   auto tiles_of = [&](int tm) { return (M + tm * 32 - 1) / (tm * 32); };
   auto trim = [&](int tm) {  // fewest padded rows among the block heights with the same tile count
@@ -471,7 +551,7 @@ bool gemm_config_fits(const GemmConfig &c, const GemmArgs &a) {
 
 size_t gemm_workspace_bytes(int M_max) {
   (void)M_max;
-  return GEMM_TICKET_BYTES + GEMM_PARTIAL_BYTES;
+  return GEMM_TICKET_BYTES + GEMM_SSQ_BYTES + GEMM_PARTIAL_BYTES;
 }
 
 size_t packed_weight_bytes(int N, int K, int dtype) {
@@ -479,11 +559,12 @@ size_t packed_weight_bytes(int N, int K, int dtype) {
   return (size_t)((N + 31) / 32) * ((K + 15) / 16) * 1024;
 }
 
-hipError_t launch_pack_weight(const void *w, void *packed, int N, int K, int glu, int dtype, hipStream_t s) {
+hipError_t launch_pack_weight(const void *w, void *packed, int N, int K, int glu, const void *col_gain, int dtype,
+                              hipStream_t s) {
   if (dtype != SF_BF16) return hipMemcpyAsync(packed, w, (size_t)N * K * sizeof(float), hipMemcpyDeviceToDevice, s);
   const size_t units = packed_weight_bytes(N, K, dtype) / 16;
   pack_weight_kernel<<<(unsigned)((units + 255) / 256), 256, 0, s>>>((const bf16_t *)w, (uint4 *)packed, N, K, units,
-                                                                     glu ? N / 2 : 0);
+                                                                     glu ? N / 2 : 0, (const bf16_t *)col_gain);
   return hipGetLastError();
 }
 

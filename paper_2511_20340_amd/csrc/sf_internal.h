@@ -12,15 +12,13 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
-// round-to-nearest-even; NaN stays NaN
-__device__ __forceinline__ bf16_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
+// round-to-nearest-even (gfx950 converts in hardware: v_cvt_pk_bf16_f32); NaN stays NaN
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16_t f2bf(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
 __device__ __forceinline__ uint32_t pack2bf(float lo, float hi) {
-  return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 template <typename T> struct Elem;
@@ -95,12 +93,17 @@ struct GemmArgs {
   // bf16 kernel choice; 0 = heuristic.  plan_M: the row count the split factor is chosen for (the
   // largest M this weight is used with), so that every M gets the same K partition; 0 = M.
   int tile = 0, split = 0, plan_M = 0;
+  // bf16 only: y = RMSNorm(x) . w^T with x the un-normalised input and the norm's gain vector already
+  // folded into w's columns at pack time; the kernel supplies the row factor 1/sqrt(mean(x^2)+eps)
+  int fused_norm = 0;
+  float norm_eps = 0.f;
 };
 struct GemmConfig {
   int tile, split;
 };
 constexpr size_t GEMM_TICKET_BYTES = 64 * 1024;
 constexpr size_t GEMM_PARTIAL_BYTES = 96u * 1024 * 1024;
+constexpr size_t GEMM_SSQ_BYTES = 1024 * 1024;  // split-K: per-split row sums of squares of the fused norm
 size_t gemm_workspace_bytes(int M_max);
 void gemm_tune(int tile, int split_k);  // tuning overrides, 0 = automatic
 int gemm_num_tiles();
@@ -109,7 +112,8 @@ GemmConfig gemm_heuristic(int M, int plan_M, int N, int K, size_t ws_bytes);
 bool gemm_config_fits(const GemmConfig &c, const GemmArgs &a);  // split-K partials fit a.ws?
 // bf16 weights are consumed in MFMA-operand-packed form (see gemm.hip); fp32 weights stay row-major
 size_t packed_weight_bytes(int N, int K, int dtype);
-hipError_t launch_pack_weight(const void *w, void *packed, int N, int K, int glu, int dtype, hipStream_t s);
+hipError_t launch_pack_weight(const void *w, void *packed, int N, int K, int glu, const void *col_gain, int dtype,
+                              hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmArgs &a, hipStream_t s);
 hipError_t launch_gemm_f32(const GemmArgs &a, hipStream_t s);
 

@@ -78,21 +78,23 @@ class Engine:
         self._keep.append(t)
         return t
 
-    def sf_pack_weight(self, w, glu=False):
-        """row-major device tensor [N,K] -> packed device buffer (kept alive by the engine)."""
+    def sf_pack_weight(self, w, glu=False, gain=None):
+        """row-major device tensor [N,K] -> packed device buffer (kept alive by the engine); gain: the
+        device gain vector [K] of the RMSNorm in front of the layer, folded into the columns (bf16)."""
         N, K = w.shape
         nb = self.lib.sf_packed_weight_bytes(self.ctx, N, K)
         es = 2 if self.dtype_id == sfb.SF_BF16 else 4
         out = torch.empty(nb // es, dtype=self.tdtype, device=self.dev)
-        sfb.check(self.lib.sf_pack_weight(self.ctx, _ptr(w), _ptr(out), N, K, int(glu), _stream()), "sf_pack_weight")
+        sfb.check(self.lib.sf_pack_weight(self.ctx, _ptr(w), _ptr(out), N, K, int(glu), _ptr(gain), _stream()),
+                  "sf_pack_weight")
         self._keep.append(out)
         return out
 
-    def _lin(self, a, glu=False):
-        """upload + pack one linear weight; the row-major copy is dropped."""
+    def _lin(self, a, glu=False, gain=None):
+        """upload + pack one linear weight (with the gains of its norm, if any); the row-major copy is dropped."""
         t = self._up(a)
         self._keep.pop()
-        p = self.sf_pack_weight(t, glu)
+        p = self.sf_pack_weight(t, glu, gain)
         torch.cuda.current_stream().synchronize()
         return p
 
@@ -102,13 +104,15 @@ class Engine:
         self._keep = []
         L = self.L
 
-        def gate_up(w, l=None):
+        # norm gains go up first: a layer that consumes a norm's output is packed with that norm's gain
+        # vector folded into its columns (bf16; the fp32 pack ignores it)
+        def gate_up(w, gain, l=None):
             if "w_gate_up" in w:
-                return self._lin(w["w_gate_up"] if l is None else w["w_gate_up"][l], glu=True)
+                return self._lin(w["w_gate_up"] if l is None else w["w_gate_up"][l], glu=True, gain=gain)
             g, u = (w["w_gate"], w["w_up"]) if l is None else (w["w_gate"][l], w["w_up"][l])
             g, u = (torch.as_tensor(np.asarray(g)) if not isinstance(g, torch.Tensor) else g,
                     torch.as_tensor(np.asarray(u)) if not isinstance(u, torch.Tensor) else u)
-            return self._lin(torch.cat([g, u], 0), glu=True)
+            return self._lin(torch.cat([g, u], 0), glu=True, gain=gain)
         T = sfb.TargetWeights()
         self.w = {}
         for n in ("embed", "lm_head", "final_norm"):
@@ -116,9 +120,10 @@ class Engine:
             setattr(T, n, self.w[n].data_ptr())
         for n in ("attn_norm", "ffn_norm"):
             self.w[n] = [self._up(tw[n][l]) for l in range(L)]
-        for n in ("wqkv", "wo", "w_down"):
+        self.w["wqkv"] = [self._lin(tw["wqkv"][l], gain=self.w["attn_norm"][l]) for l in range(L)]
+        for n in ("wo", "w_down"):
             self.w[n] = [self._lin(tw[n][l]) for l in range(L)]
-        self.w["w_gate_up"] = [gate_up(tw, l) for l in range(L)]
+        self.w["w_gate_up"] = [gate_up(tw, self.w["ffn_norm"][l], l) for l in range(L)]
         for n in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down"):
             arr = (C.c_void_p * L)(*[t.data_ptr() for t in self.w[n]])
             self._keep.append(arr)
@@ -127,12 +132,16 @@ class Engine:
         if dw is not None:
             D = sfb.DraftWeights()
             self.wd = {}
-            for n, _ in sfb.DraftWeights._fields_:
+            folded = {"wqkv": "attn_norm", "w_gate_up": "ffn_norm", "sa_wqkv": "sa_norm"}
+            names = [n for n, _ in sfb.DraftWeights._fields_]
+            for n in [x for x in names if x not in folded] + [x for x in names if x in folded]:
                 if n.startswith("sa_") and n not in dw:        # two-stage wiring not used: NULL
                     continue
                 if n == "w_gate_up":
-                    self.wd[n] = gate_up(dw)
-                elif n in ("w_ds", "w_pos", "wqkv", "wo", "w_down", "sa_wqkv", "sa_wo"):
+                    self.wd[n] = gate_up(dw, self.wd[folded[n]])
+                elif n in folded:
+                    self.wd[n] = self._lin(dw[n], gain=self.wd[folded[n]])
+                elif n in ("w_ds", "w_pos", "wo", "w_down", "sa_wo"):
                     self.wd[n] = self._lin(dw[n])
                 else:
                     self.wd[n] = self._up(dw[n])
@@ -262,6 +271,22 @@ class Engine:
         wsp, nb = self.linear_workspace(M)
         sfb.check(self.lib.sf_op_linear(self.ctx, _ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(y), M, N, K,
                                         int(out_f32), wsp, nb, _stream()), "sf_op_linear", self.ctx)
+        return y
+
+    def sf_op_rmsnorm_linear(self, x, gain, w, out_f32=False, packed=None):
+        """RMSNorm(x; gain) . w^T in one kernel (bf16).  w: row-major [N,K] device tensor, packed here with
+        the gains folded in, unless `packed` = (buffer packed that way, N) is given."""
+        M, K = x.shape
+        if packed is None:
+            N = w.shape[0]
+            w = self.sf_pack_weight(w, gain=gain)
+            self._keep.pop()
+        else:
+            w, N = packed
+        y = torch.empty(M, N, dtype=torch.float32 if out_f32 else self.tdtype, device=self.dev)
+        wsp, nb = self.linear_workspace(M)
+        sfb.check(self.lib.sf_op_rmsnorm_linear(self.ctx, _ptr(x), _ptr(w), _ptr(y), M, N, K, int(out_f32), wsp, nb,
+                                                _stream()), "sf_op_rmsnorm_linear", self.ctx)
         return y
 
     def sf_op_linear_swiglu(self, x, w_gate_up):

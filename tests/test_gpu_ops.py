@@ -123,6 +123,44 @@ def test_linear_bf16_every_tile_and_split_gives_the_same_bits(M, N, K):
         L.sf_tune_linear(0, 0)
 
 
+@pytest.mark.parametrize("M,N,K", [(160, 392, 2048), (77, 264, 200), (333, 520, 1792), (5, 128, 4096)])
+def test_rmsnorm_linear_fused(M, N, K):
+    """The decoder's norm + linear pair as one kernel: against the oracle's RMSNorm followed by its
+    linear layer, for every tile configuration and split factor, which must all agree bit for bit and
+    must not depend on the rows batched together."""
+    g = synth.rng(17, M + N)
+    x = synth.to_bf16_values(g.standard_normal((M, K), dtype=np.float32) * 3.0)
+    x[0] *= 40.0                                             # rows of very different scale
+    x[M - 1] *= 0.01
+    x = synth.to_bf16_values(x)
+    gain = synth.to_bf16_values(1.0 + 0.5 * g.standard_normal(K, dtype=np.float32))
+    w = synth.to_bf16_values(g.standard_normal((N, K), dtype=np.float32) * 0.05)
+    ref = sfo.linear(sfo.rmsnorm(x, gain, 1e-6), w)
+    eng = engine_only(shape_for("bf16", 2, 2, 64), 1, 64, 1)
+    L = sfb.lib()
+    xd, gd, wd = dev(x, "bf16"), dev(gain, "bf16"), dev(w, "bf16")
+    packed = eng.sf_pack_weight(wd, gain=gd)
+    y = eng.sf_op_rmsnorm_linear(xd, gd, None, out_f32=True, packed=(packed, N))
+    assert rel_err(to_np(y), ref) < 5e-3                      # weight * gain is rounded to bf16 once
+    yb = eng.sf_op_rmsnorm_linear(xd, gd, None, packed=(packed, N))
+    assert rel_err(to_np(yb), ref) < BF16_TOL
+    try:
+        for split in (1, 2, 4):
+            first = None
+            for tile in range(1, L.sf_linear_num_tiles() + 1):
+                sfb.check(L.sf_tune_linear(tile, split), "sf_tune_linear")
+                y = eng.sf_op_rmsnorm_linear(xd, gd, None, out_f32=True, packed=(packed, N))
+                few = eng.sf_op_rmsnorm_linear(xd[:3].contiguous(), gd, None, out_f32=True, packed=(packed, N))
+                torch.cuda.synchronize()
+                assert rel_err(to_np(y), ref) < 5e-3, (tile, split)
+                if first is None:
+                    first = y.clone()
+                assert torch.equal(y, first), (tile, split)
+                assert torch.equal(few, first[:3]), (tile, split)
+    finally:
+        L.sf_tune_linear(0, 0)
+
+
 @pytest.mark.parametrize("M,N,K", [(20, 768, 256), (77, 264, 200), (130, 1024, 1024)])
 def test_linear_f32(M, N, K):
     g = synth.rng(6, M + N)
