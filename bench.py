@@ -121,7 +121,8 @@ def profile_traffic(workload, kernel_class):
     committed rocprofv3 summary of this workload (FETCH_SIZE / WRITE_SIZE runs scaled by a copy kernel of
     known size), since counters cannot be collected from inside this process.  None if there is none."""
     import re
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"step_kernels__{workload}.md")
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                        f"step_kernels__{workload.replace('..', 'to')}.md")
     if not os.path.exists(path):
         return None
     text = open(path).read()
