@@ -203,7 +203,6 @@ void attention(Run &r, const sf_model_cfg &m, const void *q, const void *kc, con
   AttnArgs a{};
   a.q = q; a.kc = kc; a.vc = vc; a.kv_len = kv_len; a.out = out; a.part_o = part_o; a.part_ml = part_ml;
   a.B = B; a.n_q = n_q; a.Hq = m.n_q_heads; a.Hkv = m.n_kv_heads; a.hd = m.head_dim; a.cap = cap; a.mode = mode;
-  a.len_upper = len_upper;
   const int n_rt = (m.n_q_heads / m.n_kv_heads * n_q + 31) / 32;
   a.chunk_tiles = attn_chunk_tiles(B * m.n_kv_heads * n_rt, len_upper + n_q);
   const int n_tiles = (len_upper + n_q + TK - 1) / TK;

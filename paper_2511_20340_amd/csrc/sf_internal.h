@@ -57,11 +57,6 @@ __host__ __device__ constexpr int v_tile_off(int a, int c, int hd) {
 
 // fp32 mode keeps the plain layout [B][Hkv][cap][hd].
 
-struct Launch {
-  hipStream_t stream;
-  int hip_err;  // first failing hipError_t, 0 if none
-};
-
 // ---- kernel launchers (defined in the .hip files) ---------------------------------------------
 struct AttnArgs {
   const void *q;
@@ -70,7 +65,7 @@ struct AttnArgs {
   void *out;
   float *part_o;   // [B][Hkv][n_chunks][64][HD]
   float *part_ml;  // [B][Hkv][n_chunks][64][2]
-  int B, n_q, Hq, Hkv, hd, cap, mode, len_upper;
+  int B, n_q, Hq, Hkv, hd, cap, mode;
   int chunk_tiles;  // tiles of 32 keys per workgroup chunk
   int n_chunks;     // grid.x
 };
