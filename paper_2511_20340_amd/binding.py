@@ -15,7 +15,7 @@ KERNEL_CLASSES = ["linear", "attention", "attention_combine", "rmsnorm", "rope_k
 EXPORTS = [
     "sf_create", "sf_destroy", "sf_workspace_bytes", "sf_kv_cache_bytes", "sf_bind", "sf_draft_step",
     "sf_verify_step", "sf_accept_commit", "sf_kv_import", "sf_kv_export", "sf_attention_workspace_bytes",
-    "sf_op_attention", "sf_packed_weight_bytes", "sf_pack_weight", "sf_linear_workspace_bytes", "sf_op_linear", "sf_op_rmsnorm_linear", "sf_op_linear_swiglu", "sf_tune_linear", "sf_linear_num_tiles", "sf_linear_config", "sf_tune_attention", "sf_op_rmsnorm", "sf_op_rope_kv_append", "sf_op_silu_mul",
+    "sf_op_attention", "sf_packed_weight_bytes", "sf_pack_weight", "sf_linear_workspace_bytes", "sf_op_linear", "sf_op_rmsnorm_linear", "sf_op_linear_swiglu", "sf_tune_linear", "sf_linear_num_tiles", "sf_linear_config", "sf_tune_attention", "sf_op_rmsnorm", "sf_op_rope_kv_append", "sf_rope_attention_workspace_bytes", "sf_op_rope_attention", "sf_op_silu_mul",
     "sf_argmax_workspace_bytes", "sf_op_argmax", "sf_calib_copy", "sf_profile_begin", "sf_profile_end", "sf_strerror", "sf_last_hip_error", "sf_version",
 ]
 
@@ -97,6 +97,9 @@ def lib():
     L.sf_tune_attention.argtypes = [i32]
     L.sf_op_rmsnorm.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
     L.sf_op_rope_kv_append.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+    L.sf_rope_attention_workspace_bytes.argtypes = [vp, i32, i32, i32]
+    L.sf_rope_attention_workspace_bytes.restype = sz
+    L.sf_op_rope_attention.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]
     L.sf_op_silu_mul.argtypes = [vp, vp, vp, i32, i32, vp]
     L.sf_argmax_workspace_bytes.argtypes = [i32]
     L.sf_argmax_workspace_bytes.restype = sz

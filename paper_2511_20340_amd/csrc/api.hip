@@ -198,10 +198,11 @@ void norm_swiglu_in(Run &r, const sf_model_cfg &m, const void *x, const void *ga
 }
 
 void attention(Run &r, const sf_model_cfg &m, const void *q, const void *kc, const void *vc, const int32_t *kv_len,
-               void *out, float *part_o, float *part_ml, int B, int n_q, int cap, int mode, int len_upper) {
+               void *out, float *part_o, float *part_ml, int B, int n_q, int cap, int mode, int len_upper,
+               const void *qkv = nullptr, const float2 *table = nullptr) {
   if (r.st != SF_OK) return;
   AttnArgs a{};
-  a.q = q; a.kc = kc; a.vc = vc; a.kv_len = kv_len; a.out = out; a.part_o = part_o; a.part_ml = part_ml;
+  a.q = q; a.qkv = qkv; a.table = table; a.kc = kc; a.vc = vc; a.kv_len = kv_len; a.out = out; a.part_o = part_o; a.part_ml = part_ml;
   a.B = B; a.n_q = n_q; a.Hq = m.n_q_heads; a.Hkv = m.n_kv_heads; a.hd = m.head_dim; a.cap = cap; a.mode = mode;
   const int n_rt = (m.n_q_heads / m.n_kv_heads * n_q + 31) / 32;
   a.chunk_tiles = attn_chunk_tiles(B * m.n_kv_heads * n_rt, len_upper + n_q);
@@ -337,9 +338,11 @@ sf_status sf_verify_step(sf_ctx *c, const sf_state *st, int32_t k, const int32_t
     void *kc = (char *)st->tk + l * lb, *vc = (char *)st->tv + l * lb;
     norm_gemm(r, m, h, c->attn_norm[l], a, c->wqkv[l], qkv, M, nq + 2 * nkv, d, 0);
     ra.kc = kc; ra.vc = vc;
-    LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
+    // bf16: the attention kernel rotates Q and K and appends the block's K, V rows itself
+    const bool fused_rope = m.dtype == SF_BF16;
+    if (!fused_rope) LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
     attention(r, m, qr, kc, vc, st->kv_len, ao, (float *)(ws + A.part_o), (float *)(ws + A.part_ml), B, q, cap,
-              SF_MASK_CAUSAL, len_upper);
+              SF_MASK_CAUSAL, len_upper, fused_rope ? qkv : nullptr, ra.table);
     gemm(r, m.dtype, ao, c->wo[l], nullptr, h, h, M, d, nq, 0);
     norm_swiglu_in(r, m, h, c->ffn_norm[l], a, c->w_gate_up[l], gu, act, M, F, d);
     gemm(r, m.dtype, act, c->w_down[l], nullptr, h, h, M, d, F, 0);
@@ -599,6 +602,39 @@ sf_status sf_op_rope_kv_append(const sf_ctx *c, const void *qkv, const int32_t *
   Run r{c, (hipStream_t)stream};
   LAUNCH(K_ROPE, launch_rope_table(ra, r.s));
   LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
+  return r.st;
+}
+
+size_t sf_rope_attention_workspace_bytes(const sf_ctx *c, int32_t B, int32_t n_q, int32_t len_upper) {
+  if (!c || B < 1 || n_q < 1 || len_upper < 0) return 0;
+  return up((size_t)B * n_q * (c->tc.head_dim / 2) * sizeof(float2)) + sf_attention_workspace_bytes(c, B, n_q, len_upper);
+}
+
+sf_status sf_op_rope_attention(const sf_ctx *c, const void *qkv, const int32_t *kv_len, int32_t B, int32_t n_q,
+                               int32_t cap, int32_t mask, int32_t len_upper, void *kc, void *vc, void *out,
+                               void *workspace, size_t workspace_bytes, void *stream) {
+  if (!c || !qkv || !kv_len || !kc || !vc || !out || !workspace) return SF_EINVAL;
+  if (B < 1 || n_q < 1 || cap < TK || cap % TK || len_upper < 0) return SF_EINVAL;
+  if (mask != SF_MASK_CAUSAL && mask != SF_MASK_BIDIR) return SF_EINVAL;
+  if ((long)len_upper + n_q > cap) return SF_ECAPACITY;
+  const sf_model_cfg &m = c->tc;
+  if (m.dtype != SF_BF16) return SF_EUNSUPPORTED;  // fp32 keeps the two separate kernels
+  sf_status v = check_attn_shape(m, n_q);
+  if (v != SF_OK) return v;
+  if (workspace_bytes < sf_rope_attention_workspace_bytes(c, B, n_q, len_upper) || ((uintptr_t)workspace) % ALIGN)
+    return SF_ECAPACITY;
+  const size_t table_bytes = up((size_t)B * n_q * (m.head_dim / 2) * sizeof(float2));
+  const size_t need = sf_attention_workspace_bytes(c, B, n_q, len_upper);
+  const size_t rows = need / ((m.head_dim + 2) * sizeof(float));
+  float *part_o = need ? (float *)((char *)workspace + table_bytes) : nullptr;
+  float *part_ml = part_o ? part_o + rows * m.head_dim : nullptr;
+  RopeArgs ra{};
+  ra.kv_len = kv_len; ra.table = (float2 *)workspace;
+  ra.B = B; ra.n_q = n_q; ra.Hq = m.n_q_heads; ra.Hkv = m.n_kv_heads; ra.hd = m.head_dim; ra.cap = cap;
+  ra.theta = m.rope_theta;
+  Run r{c, (hipStream_t)stream};
+  LAUNCH(K_ROPE, launch_rope_table(ra, r.s));
+  attention(r, m, nullptr, kc, vc, kv_len, out, part_o, part_ml, B, n_q, cap, mask, len_upper, qkv, ra.table);
   return r.st;
 }
 

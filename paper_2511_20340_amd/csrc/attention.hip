@@ -19,12 +19,19 @@ namespace {
 constexpr int WAVES = 4;
 constexpr float NEG_INF = -__builtin_huge_valf();
 
-template <int HD>
+//
+// FUSE = 1 (the target's layers): Q is the raw output of the QKV projection, rows [q | k | v].  The
+// workgroup first rotates the block's new K rows that fall into its own tiles (RoPE, cos/sin from
+// `table`) and appends them and the V rows to the cache, then rotates its Q rows in registers (a
+// rotation pair (e, e + HD/2) sits in the same lane, k-steps s and s + KS/2).  The appended rows are
+// read back by the same workgroup after a barrier; workgroups that share (sequence, kv head) own
+// disjoint tiles, or (several row groups) write identical values.
+template <int HD, int FUSE>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
-    const bf16_t *__restrict__ Q, const uint4 *__restrict__ Kc, const uint4 *__restrict__ Vc,
+    const bf16_t *__restrict__ Q, const uint4 *Kc, const uint4 *Vc,
     const int32_t *__restrict__ kv_len, bf16_t *__restrict__ O, float *__restrict__ part_o,
     float *__restrict__ part_ml, int n_q, int Hq, int Hkv, int cap, int mode, int chunk_tiles,
-    int n_chunks, int n_rt, float scale_log2e) {
+    int n_chunks, int n_rt, float scale_log2e, const float2 *__restrict__ table) {
   constexpr int KS = HD / 16;       // k-steps of the QK^T product
   constexpr int NT = HD / 32;       // 32-column tiles of the output
   constexpr int TILE_U4 = HD * 4;   // 16-byte units per 32-key tile (32*HD*2/16)
@@ -51,9 +58,63 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
   const int qi = row_ok ? r / G : 0;    // block index of the row
   const int qh = g * G + (row_ok ? r % G : 0);
 
+  const size_t seq_base = ((size_t)b * Hkv + g) * (size_t)(cap / TK) * TILE_U4;
+  const uint4 *Kb = Kc + seq_base + lane;
+  const uint4 *Vb = Vc + seq_base + lane;
+  int t = t_begin + wave;
+  uint4 kf[KS];
+  // first K tile of this wave: before the append below when the tile lies wholly in the prefix
+  const bool early = !FUSE || (t + 1) * TK <= len;
+  if (t < t_end && early) {
+#pragma unroll
+    for (int s = 0; s < KS; ++s) kf[s] = Kb[(size_t)t * TILE_U4 + s * 64];
+  }
+
   // Q^T operand: lane (n, h), k-step s holds features [(2s+h)*8, +8) of row r
   bf16x8 qf[KS];
-  {
+  if (FUSE) {
+    constexpr int HALF = HD / 2;
+    const size_t row_stride = (size_t)(Hq + 2 * Hkv) * HD;
+    // the block's new rows that live in this workgroup's tiles: rotate K, append K and V
+    bf16_t *Kw = reinterpret_cast<bf16_t *>(const_cast<uint4 *>(Kc)) + seq_base * 8;
+    bf16_t *Vw = reinterpret_cast<bf16_t *>(const_cast<uint4 *>(Vc)) + seq_base * 8;
+    for (int x = tid; x < n_q * HALF; x += 256) {
+      const int j = x / HALF, e = x % HALF;
+      const int pos = len + j, tile = pos / TK, a_in = pos % TK;
+      if (tile < t_begin || tile >= t_end) continue;
+      const bf16_t *src = Q + ((size_t)b * n_q + j) * row_stride + (size_t)(Hq + g) * HD;
+      const float2 cs = table[((size_t)b * n_q + j) * HALF + e];
+      const float a = bf2f(src[e]), bb = bf2f(src[e + HALF]);
+      const size_t base = (size_t)tile * (TK * HD);
+      float k0, k1;
+      rope_pair(a, bb, cs, k0, k1);
+      Kw[base + k_tile_off(a_in, e)] = f2bf(k0);
+      Kw[base + k_tile_off(a_in, e + HALF)] = f2bf(k1);
+      Vw[base + v_tile_off(a_in, e, HD)] = src[(size_t)Hkv * HD + e];
+      Vw[base + v_tile_off(a_in, e + HALF, HD)] = src[(size_t)Hkv * HD + e + HALF];
+    }
+    // this lane's Q features: a rotation pair sits in k-steps s and s + KS/2 of the same lane
+    const uint4 *qp = reinterpret_cast<const uint4 *>(Q + ((size_t)b * n_q + qi) * row_stride + (size_t)qh * HD);
+    const float2 *tab = table + ((size_t)b * n_q + qi) * HALF;
+#pragma unroll
+    for (int s = 0; s < KS / 2; ++s) {
+      const uint4 lo4 = row_ok ? qp[2 * s + h] : make_uint4(0, 0, 0, 0);
+      const uint4 hi4 = row_ok ? qp[2 * (s + KS / 2) + h] : make_uint4(0, 0, 0, 0);
+      const bf16x8 lo = __builtin_bit_cast(bf16x8, lo4), hi = __builtin_bit_cast(bf16x8, hi4);
+      bf16x8 rl, rh;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float2 cs = tab[(2 * s + h) * 8 + i];
+        float q0, q1;
+        rope_pair((float)lo[i], (float)hi[i], cs, q0, q1);
+        rl[i] = (__bf16)q0;
+        rh[i] = (__bf16)q1;
+      }
+      qf[s] = rl;
+      qf[s + KS / 2] = rh;
+    }
+    __syncthreads();  // the appended rows are visible to every wave of the workgroup
+  } else {
     const uint4 *qp = reinterpret_cast<const uint4 *>(Q + (((size_t)b * n_q + qi) * Hq + qh) * HD);
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
@@ -62,10 +123,6 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     }
   }
 
-  const size_t seq_base = ((size_t)b * Hkv + g) * (size_t)(cap / TK) * TILE_U4;
-  const uint4 *Kb = Kc + seq_base + lane;
-  const uint4 *Vb = Vc + seq_base + lane;
-
   f32x16 acc[NT];
 #pragma unroll
   for (int c = 0; c < NT; ++c)
@@ -73,13 +130,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
   float m_run = NEG_INF, l_run = 0.f;
 
-  int t = t_begin + wave;
-  uint4 kf[KS];
-  if (t < t_end) {
-#pragma unroll
-    for (int s = 0; s < KS; ++s) kf[s] = Kb[(size_t)t * TILE_U4 + s * 64];
-  }
-  for (; t < t_end; t += WAVES) {
+  auto tile_step = [&](const int t, const int t_lim) __attribute__((always_inline)) {
     uint4 vf[KS];  // 2*NT == KS units
 #pragma unroll
     for (int s = 0; s < KS; ++s) vf[s] = Vb[(size_t)t * TILE_U4 + s * 64];
@@ -93,7 +144,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
 
     // prefetch the next tile's K while the softmax runs
     const int tn = t + WAVES;
-    if (tn < t_end) {
+    if (tn < t_lim) {
 #pragma unroll
       for (int s = 0; s < KS; ++s) kf[s] = Kb[(size_t)tn * TILE_U4 + s * 64];
     }
@@ -152,7 +203,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
       for (int c = 0; c < NT; ++c)
         acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[u * NT + c]), pf[u],
                                                          acc[c], 0, 0, 0);
+  };
+  if (FUSE && t < t_end && !early) {
+#pragma unroll
+    for (int s = 0; s < KS; ++s) kf[s] = Kb[(size_t)t * TILE_U4 + s * 64];
   }
+  for (; t < t_end; t += WAVES) tile_step(t, t_end);
 
   // ---- merge the 4 waves through LDS --------------------------------------------------------
   float *lds_o = lds;                           // [WAVES][32][LROW]
@@ -354,23 +410,29 @@ hipError_t launch_attention_bf16(const AttnArgs &a, hipStream_t s) {
   const size_t lds = (size_t)WAVES * 32 * (a.hd + 4 + 2) * sizeof(float);
   static bool attr_done = false;
   if (!attr_done) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bf16_kernel<128>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bf16_kernel<128, 0>),
                         hipFuncAttributeMaxDynamicSharedMemorySize, WAVES * 32 * (128 + 6) * 4);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bf16_kernel<64>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bf16_kernel<128, 1>),
+                        hipFuncAttributeMaxDynamicSharedMemorySize, WAVES * 32 * (128 + 6) * 4);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bf16_kernel<64, 0>),
+                        hipFuncAttributeMaxDynamicSharedMemorySize, WAVES * 32 * (64 + 6) * 4);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bf16_kernel<64, 1>),
                         hipFuncAttributeMaxDynamicSharedMemorySize, WAVES * 32 * (64 + 6) * 4);
     attr_done = true;
   }
+  // a.qkv: the raw QKV projection; the kernel rotates and appends the block's rows itself
+  const bf16_t *q = (const bf16_t *)(a.qkv ? a.qkv : a.q);
+#define SF_ATTN_LAUNCH(HD_, FUSE_)                                                                              \
+  attn_bf16_kernel<HD_, FUSE_><<<grid, block, lds, s>>>(q, (const uint4 *)a.kc, (const uint4 *)a.vc, a.kv_len, \
+                                                        (bf16_t *)a.out, a.part_o, a.part_ml, a.n_q, a.Hq,     \
+                                                        a.Hkv, a.cap, a.mode, a.chunk_tiles, a.n_chunks, n_rt, \
+                                                        scale_log2e, a.table)
   if (a.hd == 128) {
-    attn_bf16_kernel<128><<<grid, block, lds, s>>>((const bf16_t *)a.q, (const uint4 *)a.kc, (const uint4 *)a.vc,
-                                                   a.kv_len, (bf16_t *)a.out, a.part_o, a.part_ml, a.n_q, a.Hq,
-                                                   a.Hkv, a.cap, a.mode, a.chunk_tiles, a.n_chunks, n_rt,
-                                                   scale_log2e);
+    if (a.qkv) SF_ATTN_LAUNCH(128, 1); else SF_ATTN_LAUNCH(128, 0);
   } else {
-    attn_bf16_kernel<64><<<grid, block, lds, s>>>((const bf16_t *)a.q, (const uint4 *)a.kc, (const uint4 *)a.vc,
-                                                  a.kv_len, (bf16_t *)a.out, a.part_o, a.part_ml, a.n_q, a.Hq,
-                                                  a.Hkv, a.cap, a.mode, a.chunk_tiles, a.n_chunks, n_rt,
-                                                  scale_log2e);
+    if (a.qkv) SF_ATTN_LAUNCH(64, 1); else SF_ATTN_LAUNCH(64, 0);
   }
+#undef SF_ATTN_LAUNCH
   return hipGetLastError();
 }
 

@@ -149,8 +149,10 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const T *__restrict__ QKV,
     const int hh = x / half, e = x % half;
     const float2 cs = tab[e];
     const float a = Elem<T>::ld(src + hh * hd + e), bb = Elem<T>::ld(src + hh * hd + e + half);
-    Elem<T>::st(Qo + (size_t)row * nq_cols + hh * hd + e, a * cs.x - bb * cs.y);
-    Elem<T>::st(Qo + (size_t)row * nq_cols + hh * hd + e + half, bb * cs.x + a * cs.y);
+    float q0, q1;
+    rope_pair(a, bb, cs, q0, q1);
+    Elem<T>::st(Qo + (size_t)row * nq_cols + hh * hd + e, q0);
+    Elem<T>::st(Qo + (size_t)row * nq_cols + hh * hd + e + half, q1);
   }
   if (!valid) return;
   const size_t tile = pos / TK;
@@ -159,7 +161,8 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const T *__restrict__ QKV,
     const int g = x / half, e = x % half;
     const float2 cs = tab[e];
     const float a = Elem<T>::ld(src + nq_cols + g * hd + e), bb = Elem<T>::ld(src + nq_cols + g * hd + e + half);
-    const float k0 = a * cs.x - bb * cs.y, k1 = bb * cs.x + a * cs.y;
+    float k0, k1;
+    rope_pair(a, bb, cs, k0, k1);
     const float v0 = Elem<T>::ld(src + nq_cols + nkv + g * hd + e);
     const float v1 = Elem<T>::ld(src + nq_cols + nkv + g * hd + e + half);
     if (sizeof(T) == 2) {

@@ -21,6 +21,13 @@ __device__ __forceinline__ uint32_t pack2bf(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+// One RoPE pair (x[e], x[e + hd/2]) turned by the angle whose (cos, sin) is cs.  Explicit fused
+// multiply-adds: every kernel that rotates must round the same way.
+__device__ __forceinline__ void rope_pair(float a, float b, float2 cs, float &lo, float &hi) {
+  lo = __builtin_fmaf(a, cs.x, -(b * cs.y));
+  hi = __builtin_fmaf(b, cs.x, a * cs.y);
+}
+
 template <typename T> struct Elem;
 template <> struct Elem<bf16_t> {
   static __device__ __forceinline__ float ld(const bf16_t *p) { return bf2f(*p); }
@@ -60,6 +67,10 @@ __host__ __device__ constexpr int v_tile_off(int a, int c, int hd) {
 // ---- kernel launchers (defined in the .hip files) ---------------------------------------------
 struct AttnArgs {
   const void *q;
+  // bf16 only, optional: the raw QKV projection rows [q | k | v] and the cos/sin table of their
+  // positions.  When set, q is ignored and the kernel rotates Q and K and appends K, V itself.
+  const void *qkv;
+  const float2 *table;
   const void *kc, *vc;
   const int32_t *kv_len;
   void *out;

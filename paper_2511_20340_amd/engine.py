@@ -325,6 +325,21 @@ class Engine:
         self._keep_ws = ws
         return q_out
 
+    def sf_op_rope_attention(self, qkv, kv_len, n_q, kc, vc, mask, len_upper=None):
+        """Rotate + append + attend in one kernel (bf16).  qkv [B*n_q,(Hq+2Hkv)*hd]; returns [B,n_q,Hq,hd]."""
+        B = kv_len.shape[0]
+        if len_upper is None:
+            len_upper = int(kv_len.max().item())
+        need = self.lib.sf_rope_attention_workspace_bytes(self.ctx, B, n_q, len_upper)
+        ws = torch.empty(need + 256, dtype=torch.uint8, device=self.dev)
+        p = ws.data_ptr() + (-ws.data_ptr()) % 256
+        out = torch.empty(B, n_q, self.Hq, self.hd, dtype=self.tdtype, device=self.dev)
+        sfb.check(self.lib.sf_op_rope_attention(self.ctx, _ptr(qkv), _ptr(kv_len), B, n_q, self.cap, mask, len_upper,
+                                                _ptr(kc), _ptr(vc), _ptr(out), C.c_void_p(p), need, _stream()),
+                  "sf_op_rope_attention", self.ctx)
+        self._keep_ws = ws
+        return out
+
     def sf_op_silu_mul(self, gu):
         M, F2 = gu.shape
         act = torch.empty(M, F2 // 2, dtype=self.tdtype, device=self.dev)

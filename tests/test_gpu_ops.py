@@ -259,3 +259,62 @@ def test_argmax_bit_exact(V):
     ids = eng.sf_op_argmax(torch.from_numpy(lg).cuda()).cpu().numpy()
     want = np.array([sfo.argmax(lg[r]) for r in range(M)], np.int32)
     np.testing.assert_array_equal(ids, want)
+
+
+@pytest.mark.parametrize("mode", [sfb.SF_MASK_CAUSAL, sfb.SF_MASK_BIDIR])
+@pytest.mark.parametrize("Hq,Hkv,hd,nq,chunk", [(8, 2, 64, 5, 0), (8, 2, 128, 5, 0), (16, 2, 128, 5, 0),
+                                                 (8, 2, 64, 5, 16), (8, 2, 128, 7, 16), (4, 4, 128, 1, 0)])
+def test_rope_attention_fused(mode, Hq, Hkv, hd, nq, chunk):
+    """The target layers' kernel (rotate Q and K, append K and V, attend) against the oracle's rope +
+    attention and, bit for bit, against the two separate kernels.  Lengths: empty prefix, a block that
+    ends on / crosses a tile boundary, one that crosses a split-KV chunk boundary (510 with 16-tile
+    chunks), a long ragged one, and a block that fills the cache to its last slot."""
+    cap = 2048
+    lens = np.array([0, 27, 30, 32, 510, 1500, cap - nq], np.int32)
+    B = len(lens)
+    g = synth.rng(21, Hq * hd + nq)
+    qkv = synth.to_bf16_values(g.standard_normal((B * nq, (Hq + 2 * Hkv) * hd), dtype=np.float32))
+    _, kc, vc = synth.random_qkv(4, B, 1, Hq, Hkv, hd, cap, "bf16")
+    for b in range(B):                       # dead slots hold NaN: nothing past the block may be read
+        kc[b, :, lens[b] + nq:] = np.nan
+        vc[b, :, lens[b] + nq:] = np.nan
+    pos = (lens[:, None] + np.arange(nq)[None]).reshape(-1).astype(np.int32)
+    nqc, nkv = Hq * hd, Hkv * hd
+    q_ref = synth.to_bf16_values(sfo.rope(qkv[:, :nqc].reshape(-1, Hq, hd), pos).astype(np.float32))
+    k_ref = synth.to_bf16_values(sfo.rope(qkv[:, nqc:nqc + nkv].reshape(-1, Hkv, hd), pos).astype(np.float32))
+    v_ref = qkv[:, nqc + nkv:].reshape(-1, Hkv, hd)
+    kc_ref, vc_ref = np.nan_to_num(kc.astype(np.float64)), np.nan_to_num(vc.astype(np.float64))
+    for b in range(B):
+        for i in range(nq):
+            kc_ref[b, :, lens[b] + i] = k_ref[b * nq + i]
+            vc_ref[b, :, lens[b] + i] = v_ref[b * nq + i]
+    ref = sfo.attention(q_ref.reshape(B, nq, Hq, hd), kc_ref, vc_ref, lens, mode)
+
+    kvl = torch.from_numpy(lens).cuda()
+    L = sfb.lib()
+    L.sf_tune_attention(chunk)
+    try:
+        eng = engine_only(shape_for("bf16", Hq, Hkv, hd), B, cap, max(nq - 1, 1))
+        eng.sf_kv_import(kc, "dk"); eng.sf_kv_import(vc, "dv")
+        out = eng.sf_op_rope_attention(dev(qkv, "bf16"), kvl, nq, eng.dk, eng.dv, mode)
+        torch.cuda.synchronize()
+        got, kg, vg = to_np(out), to_np(eng.sf_kv_export("dk")), to_np(eng.sf_kv_export("dv"))
+        # the two-kernel route on a second pair of caches
+        eng2 = engine_only(shape_for("bf16", Hq, Hkv, hd), B, cap, max(nq - 1, 1))
+        eng2.sf_kv_import(kc, "dk"); eng2.sf_kv_import(vc, "dv")
+        q_rot = eng2.sf_op_rope_kv_append(dev(qkv, "bf16"), kvl, nq, eng2.dk, eng2.dv)
+        out2 = eng2.sf_op_attention(q_rot.view(B, nq, Hq, hd), eng2.dk, eng2.dv, kvl, nq, mode)
+        torch.cuda.synchronize()
+        got2, kg2, vg2 = to_np(out2), to_np(eng2.sf_kv_export("dk")), to_np(eng2.sf_kv_export("dv"))
+    finally:
+        L.sf_tune_attention(0)
+    assert np.all(np.isfinite(got))
+    assert rel_err(got, ref) < BF16_TOL
+    live = np.zeros((B, cap), bool)
+    for b in range(B):
+        live[b, :lens[b] + nq] = True
+    for a, c in ((kg, kg2), (vg, vg2)):
+        np.testing.assert_array_equal(a.transpose(0, 2, 1, 3)[live], c.transpose(0, 2, 1, 3)[live])
+    assert rel_err(kg.transpose(0, 2, 1, 3)[live], kc_ref.transpose(0, 2, 1, 3)[live]) < BF16_TOL
+    np.testing.assert_array_equal(vg.transpose(0, 2, 1, 3)[live], vc_ref.transpose(0, 2, 1, 3)[live])
+    np.testing.assert_array_equal(got, got2)
