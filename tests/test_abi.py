@@ -111,6 +111,34 @@ def test_steps_reject_bad_state_before_launching_anything():
     L.sf_destroy(ctx)
 
 
+def test_rope_attention_op_validates_before_launching_anything():
+    L = sfb.lib()
+    fake = 0x10000
+    bf = dict(dtype=sfb.SF_BF16, n_q_heads=8, n_kv_heads=2, head_dim=64, d_model=512)
+    st, ctx = create(cfg(**bf), cfg(n_layers=1, **bf))
+    assert st == sfb.SF_OK
+    need = L.sf_rope_attention_workspace_bytes(ctx, 4, 5, 100)
+    assert need >= 4 * 5 * 32 * 8                      # at least the cos/sin table
+    assert L.sf_rope_attention_workspace_bytes(ctx, 0, 5, 100) == 0
+    call = lambda **kw: L.sf_op_rope_attention(ctx, kw.get("qkv", fake), fake, kw.get("B", 4), kw.get("n_q", 5),
+                                               kw.get("cap", 128), kw.get("mask", sfb.SF_MASK_BIDIR),
+                                               kw.get("upper", 100), fake, fake, fake, kw.get("ws", fake),
+                                               kw.get("ws_bytes", need), None)
+    assert call(qkv=None) == sfb.SF_EINVAL
+    assert call(cap=100) == sfb.SF_EINVAL              # not a multiple of the 32-key tile
+    assert call(mask=9) == sfb.SF_EINVAL
+    assert call(upper=124) == sfb.SF_ECAPACITY         # 124 + 5 > 128
+    assert call(ws_bytes=need - 1) == sfb.SF_ECAPACITY
+    assert call(ws=fake + 16) == sfb.SF_ECAPACITY      # misaligned workspace
+    assert call(n_q=17) == sfb.SF_EUNSUPPORTED         # 4 query heads per kv head x 17 rows > 64
+    L.sf_destroy(ctx)
+    st, ctx32 = create(cfg(), cfg(n_layers=1))         # fp32 keeps the two separate kernels
+    assert st == sfb.SF_OK
+    assert L.sf_op_rope_attention(ctx32, fake, fake, 4, 5, 128, sfb.SF_MASK_BIDIR, 100, fake, fake, fake, fake,
+                                  1 << 20, None) == sfb.SF_EUNSUPPORTED
+    L.sf_destroy(ctx32)
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(sfb, "_lib", None)
     monkeypatch.setattr(sfb, "LIB_PATH", "/nonexistent/libspecformer.so")
