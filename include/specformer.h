@@ -268,7 +268,7 @@ sf_status sf_op_rope_kv_append(const sf_ctx *ctx, const void *qkv, const int32_t
  * [kv_len[b], kv_len[b]+n_q) of one layer's tiled caches (kc, vc: dev, written), and the hybrid-mask
  * attention of the rotated rows over the cached context plus the block.  qkv: dev elem
  * [B*n_q][(Hq+2Hkv)*hd] (read only); out: dev elem [B][n_q][Hq][hd].  workspace: dev, 256-byte
- * aligned, sf_rope_attention_workspace_bytes (cos/sin table + split-KV partials); host_len_upper
+ * aligned, sf_rope_attention_workspace_bytes (cos/sin table, length ranking, split-KV partials); host_len_upper
  * >= max kv_len, host_len_upper + n_q <= cap (SF_ECAPACITY otherwise). */
 size_t sf_rope_attention_workspace_bytes(const sf_ctx *ctx, int32_t B, int32_t n_q, int32_t host_len_upper);
 sf_status sf_op_rope_attention(const sf_ctx *ctx, const void *qkv, const int32_t *kv_len, int32_t B,

@@ -41,7 +41,7 @@ size_t esize(int dtype) { return dtype == SF_BF16 ? 2 : 4; }
 // (B*(max_k+1) rows) and draft-slot (B*k rows) uses; draft and verify run back to back on one
 // stream, so they share it.
 struct Arena {
-  size_t h, a, qkv, qr, ao, gu, act, table, part_o, part_ml, pmax, pidx;  // shared
+  size_t h, a, qkv, qr, ao, gu, act, table, order, part_o, part_ml, pmax, pidx;  // shared
   size_t f4, x, kvc, xl, s0, dlogits;                                    // draft only
   size_t x_last, id_last, q1, qr1, ao1, len_m1, zeros, kc2, vc2;         // draft, two-stage wiring
   size_t gemm_ws, gemm_ws_bytes;
@@ -72,6 +72,7 @@ Arena plan(const sf_ctx *c, int B, int k, int cap) {
   a.gu = take(m.dtype == SF_F32 ? M * 2 * F * sizeof(float) : 0);  // bf16 gates in the GEMM epilogue
   a.act = take(M * F * es);
   a.table = take(Mx * (m.head_dim / 2) * sizeof(float2));
+  a.order = take((size_t)B * sizeof(int32_t));
   const int G = m.n_q_heads / m.n_kv_heads;
   size_t part = m.dtype == SF_BF16 ? attn_workspace_bytes(B, m.n_kv_heads, m.head_dim, G, k + 1, cap) : 0;
   const size_t rows_part = part / ((m.head_dim + 2) * sizeof(float));
@@ -199,10 +200,10 @@ void norm_swiglu_in(Run &r, const sf_model_cfg &m, const void *x, const void *ga
 
 void attention(Run &r, const sf_model_cfg &m, const void *q, const void *kc, const void *vc, const int32_t *kv_len,
                void *out, float *part_o, float *part_ml, int B, int n_q, int cap, int mode, int len_upper,
-               const void *qkv = nullptr, const float2 *table = nullptr) {
+               const void *qkv = nullptr, const float2 *table = nullptr, const int32_t *order = nullptr) {
   if (r.st != SF_OK) return;
   AttnArgs a{};
-  a.q = q; a.qkv = qkv; a.table = table; a.kc = kc; a.vc = vc; a.kv_len = kv_len; a.out = out; a.part_o = part_o; a.part_ml = part_ml;
+  a.q = q; a.qkv = qkv; a.table = table; a.order = order; a.kc = kc; a.vc = vc; a.kv_len = kv_len; a.out = out; a.part_o = part_o; a.part_ml = part_ml;
   a.B = B; a.n_q = n_q; a.Hq = m.n_q_heads; a.Hkv = m.n_kv_heads; a.hd = m.head_dim; a.cap = cap; a.mode = mode;
   const int n_rt = (m.n_q_heads / m.n_kv_heads * n_q + 31) / 32;
   a.chunk_tiles = attn_chunk_tiles(B * m.n_kv_heads * n_rt, len_upper + n_q);
@@ -328,6 +329,10 @@ sf_status sf_verify_step(sf_ctx *c, const sf_state *st, int32_t k, const int32_t
   ra.qkv = qkv; ra.q_out = qr; ra.kv_len = st->kv_len; ra.n_new = nullptr; ra.table = (float2 *)(ws + A.table);
   ra.B = B; ra.n_q = q; ra.Hq = m.n_q_heads; ra.Hkv = m.n_kv_heads; ra.hd = m.head_dim; ra.cap = cap;
   ra.kv_only = 0; ra.pos_mode = 0; ra.theta = m.rope_theta;
+  // bf16, more attention workgroups than the chip holds at once (2 per CU): the table kernel also ranks
+  // the sequences by length, and the attention launches of this call start the longest first
+  const int attn_groups = B * m.n_kv_heads * ((m.n_q_heads / m.n_kv_heads * q + 31) / 32);
+  ra.order = m.dtype == SF_BF16 && attn_groups > 512 ? (int32_t *)(ws + A.order) : nullptr;
   LAUNCH(K_ROPE, launch_rope_table(ra, r.s));
   const int hook_layer[4] = {0, L / 2, L - 1, L};
   const size_t lb = kv_layer_bytes(m, B, cap);
@@ -342,7 +347,7 @@ sf_status sf_verify_step(sf_ctx *c, const sf_state *st, int32_t k, const int32_t
     const bool fused_rope = m.dtype == SF_BF16;
     if (!fused_rope) LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
     attention(r, m, qr, kc, vc, st->kv_len, ao, (float *)(ws + A.part_o), (float *)(ws + A.part_ml), B, q, cap,
-              SF_MASK_CAUSAL, len_upper, fused_rope ? qkv : nullptr, ra.table);
+              SF_MASK_CAUSAL, len_upper, fused_rope ? qkv : nullptr, ra.table, ra.order);
     gemm(r, m.dtype, ao, c->wo[l], nullptr, h, h, M, d, nq, 0);
     norm_swiglu_in(r, m, h, c->ffn_norm[l], a, c->w_gate_up[l], gu, act, M, F, d);
     gemm(r, m.dtype, act, c->w_down[l], nullptr, h, h, M, d, F, 0);
@@ -607,7 +612,8 @@ sf_status sf_op_rope_kv_append(const sf_ctx *c, const void *qkv, const int32_t *
 
 size_t sf_rope_attention_workspace_bytes(const sf_ctx *c, int32_t B, int32_t n_q, int32_t len_upper) {
   if (!c || B < 1 || n_q < 1 || len_upper < 0) return 0;
-  return up((size_t)B * n_q * (c->tc.head_dim / 2) * sizeof(float2)) + sf_attention_workspace_bytes(c, B, n_q, len_upper);
+  return up((size_t)B * n_q * (c->tc.head_dim / 2) * sizeof(float2)) + up((size_t)B * sizeof(int32_t)) +
+         sf_attention_workspace_bytes(c, B, n_q, len_upper);
 }
 
 sf_status sf_op_rope_attention(const sf_ctx *c, const void *qkv, const int32_t *kv_len, int32_t B, int32_t n_q,
@@ -624,17 +630,18 @@ sf_status sf_op_rope_attention(const sf_ctx *c, const void *qkv, const int32_t *
   if (workspace_bytes < sf_rope_attention_workspace_bytes(c, B, n_q, len_upper) || ((uintptr_t)workspace) % ALIGN)
     return SF_ECAPACITY;
   const size_t table_bytes = up((size_t)B * n_q * (m.head_dim / 2) * sizeof(float2));
+  const size_t order_bytes = up((size_t)B * sizeof(int32_t));
   const size_t need = sf_attention_workspace_bytes(c, B, n_q, len_upper);
   const size_t rows = need / ((m.head_dim + 2) * sizeof(float));
-  float *part_o = need ? (float *)((char *)workspace + table_bytes) : nullptr;
+  float *part_o = need ? (float *)((char *)workspace + table_bytes + order_bytes) : nullptr;
   float *part_ml = part_o ? part_o + rows * m.head_dim : nullptr;
   RopeArgs ra{};
-  ra.kv_len = kv_len; ra.table = (float2 *)workspace;
+  ra.kv_len = kv_len; ra.table = (float2 *)workspace; ra.order = (int32_t *)((char *)workspace + table_bytes);
   ra.B = B; ra.n_q = n_q; ra.Hq = m.n_q_heads; ra.Hkv = m.n_kv_heads; ra.hd = m.head_dim; ra.cap = cap;
   ra.theta = m.rope_theta;
   Run r{c, (hipStream_t)stream};
   LAUNCH(K_ROPE, launch_rope_table(ra, r.s));
-  attention(r, m, nullptr, kc, vc, kv_len, out, part_o, part_ml, B, n_q, cap, mask, len_upper, qkv, ra.table);
+  attention(r, m, nullptr, kc, vc, kv_len, out, part_o, part_ml, B, n_q, cap, mask, len_upper, qkv, ra.table, ra.order);
   return r.st;
 }
 

@@ -31,14 +31,15 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     const bf16_t *__restrict__ Q, const uint4 *Kc, const uint4 *Vc,
     const int32_t *__restrict__ kv_len, bf16_t *__restrict__ O, float *__restrict__ part_o,
     float *__restrict__ part_ml, int n_q, int Hq, int Hkv, int cap, int mode, int chunk_tiles,
-    int n_chunks, int n_rt, float scale_log2e, const float2 *__restrict__ table) {
+    int n_chunks, int n_rt, float scale_log2e, const float2 *__restrict__ table,
+    const int32_t *__restrict__ order) {
   constexpr int KS = HD / 16;       // k-steps of the QK^T product
   constexpr int NT = HD / 32;       // 32-column tiles of the output
   constexpr int TILE_U4 = HD * 4;   // 16-byte units per 32-key tile (32*HD*2/16)
   constexpr int LROW = HD + 4;      // padded LDS row (floats)
   extern __shared__ float lds[];    // [WAVES][32][LROW] + [WAVES][32][2]
 
-  const int b = blockIdx.z;
+  const int b = order ? order[blockIdx.z] : blockIdx.z;  // longest sequences first, if the caller ranked them
   const int g = blockIdx.y / n_rt, rt = blockIdx.y % n_rt;
   const int chunk = blockIdx.x;
   const int G = Hq / Hkv;
@@ -426,7 +427,7 @@ hipError_t launch_attention_bf16(const AttnArgs &a, hipStream_t s) {
   attn_bf16_kernel<HD_, FUSE_><<<grid, block, lds, s>>>(q, (const uint4 *)a.kc, (const uint4 *)a.vc, a.kv_len, \
                                                         (bf16_t *)a.out, a.part_o, a.part_ml, a.n_q, a.Hq,     \
                                                         a.Hkv, a.cap, a.mode, a.chunk_tiles, a.n_chunks, n_rt, \
-                                                        scale_log2e, a.table)
+                                                        scale_log2e, a.table, a.order)
   if (a.hd == 128) {
     if (a.qkv) SF_ATTN_LAUNCH(128, 1); else SF_ATTN_LAUNCH(128, 0);
   } else {

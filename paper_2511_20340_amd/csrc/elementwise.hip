@@ -112,9 +112,24 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *__restrict__ X, c
 }
 
 // cos/sin of pos * theta^(-2i/hd), evaluated in double so that large positions stay exact to fp32.
+// One extra workgroup (when `order` is given) ranks the sequences by descending length, ties by
+// index: order[rank] = b.  The attention kernel starts the longest sequences first, which evens out
+// the tail of a ragged batch.
 __global__ void rope_table_kernel(float2 *__restrict__ table, const int32_t *__restrict__ kv_len,
                                   const int32_t *__restrict__ n_new, int B, int n_q, int half, int pos_mode,
-                                  double log2_theta) {
+                                  double log2_theta, int32_t *__restrict__ order) {
+  if (order && blockIdx.x == gridDim.x - 1) {
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+      const int mine = kv_len[b];
+      int rank = 0;
+      for (int j = 0; j < B; ++j) {
+        const int other = kv_len[j];
+        rank += (other > mine || (other == mine && j < b)) ? 1 : 0;
+      }
+      order[rank] = b;
+    }
+    return;
+  }
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= B * n_q * half) return;
   const int i = idx % half, row = idx / half, b = row / n_q, r = row % n_q;
@@ -280,8 +295,8 @@ hipError_t launch_rmsnorm(const NormArgs &a, int dtype, hipStream_t s) {
 hipError_t launch_rope_table(const RopeArgs &a, hipStream_t s) {
   const int half = a.hd / 2;
   const int n = a.B * a.n_q * half;
-  rope_table_kernel<<<(n + 255) / 256, 256, 0, s>>>(a.table, a.kv_len, a.n_new, a.B, a.n_q, half, a.pos_mode,
-                                                    log2((double)a.theta));
+  rope_table_kernel<<<(n + 255) / 256 + (a.order ? 1 : 0), 256, 0, s>>>(a.table, a.kv_len, a.n_new, a.B, a.n_q, half,
+                                                                        a.pos_mode, log2((double)a.theta), a.order);
   return hipGetLastError();
 }
 

@@ -71,6 +71,7 @@ struct AttnArgs {
   // positions.  When set, q is ignored and the kernel rotates Q and K and appends K, V itself.
   const void *qkv;
   const float2 *table;
+  const int32_t *order;  // bf16 only, optional [B]: a permutation of the sequences, workgroups of order[0] start first
   const void *kc, *vc;
   const int32_t *kv_len;
   void *out;
@@ -146,6 +147,7 @@ struct RopeArgs {
   const int32_t *kv_len;
   const int32_t *n_new;  // pos_mode 1
   float2 *table;         // [M][hd/2] cos,sin scratch
+  int32_t *order;        // optional [B]: filled with the sequences in descending kv_len order
   int B, n_q, Hq, Hkv, hd, cap;
   int kv_only;   // rows carry only K,V
   int pos_mode;  // 0: pos = kv_len[b]+i, all rows valid; 1: pos = kv_len[b]-n_new[b]+i, valid iff i<n_new[b]

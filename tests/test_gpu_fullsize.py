@@ -217,6 +217,58 @@ def test_1b_full_step_two_sequences_against_oracle_and_graph_replay():
     assert torch.equal(acc2, eager[2]) and torch.equal(out2, eager[3]) and torch.equal(eng.kv_len, eager[4])
 
 
+# ---- a verify pass over more attention workgroups than the chip holds: sequences ranked by length ---------
+def test_verify_with_length_ranked_attention_three_sequences_against_oracle():
+    """272 ragged sequences x 2 kv heads = 544 attention workgroups: above 512 the verify pass starts the
+    longest sequences first (a device-side ranking).  The longest, the shortest and a middle sequence,
+    sitting at scattered batch indices, must still come out as the oracle computes them one by one."""
+    m = synth.ModelShape("ranked", 2, 256, 4, 2, 64, 512, 512, "bf16")
+    B, k, cap = 272, 4, 768
+    probes = [3, 137, 260]
+    Bp = len(probes)
+    g = synth.rng(31, 5)
+    lens = g.integers(5, 700, B).astype(np.int32)
+    lens[probes[0]], lens[probes[1]], lens[probes[2]] = 730, 1, 333
+    tw, dw = synth.target_weights(m, 31), synth.draft_weights(m, k, 31)
+    orc = sfo.Oracle(m.cfg(), tw, dw, Bp, cap, q_max=k + 1, round_bf16=True)
+    ref = sfo.Oracle(m.cfg(), tw, dw, Bp, cap, q_max=k + 1, round_bf16=False)
+    for name in ("tk", "tv"):
+        a = getattr(orc, name)
+        a[...] = synth.to_bf16_values(g.standard_normal(a.shape, dtype=np.float32))
+    orc.kv_len[:] = lens[probes]
+    orc.n_new[:] = 1
+    orc.pending[:] = g.integers(0, m.vocab, Bp)
+    ref.restore(orc.snapshot())
+    draft_o = g.integers(0, m.vocab, (Bp, k)).astype(np.int32)
+
+    eng = Engine(m.cfg(), B, cap, k)
+    eng.bind(tw, dw)
+    for which, src in (("tk", orc.tk), ("tv", orc.tv)):
+        for l in range(m.n_layers):
+            plain = device_normal((B, m.n_kv_heads, cap, m.head_dim), 300 + 7 * l + len(which))
+            plain[probes] = torch.from_numpy(src[l].astype(np.float32)).cuda().to(torch.bfloat16)
+            eng.sf_kv_import(plain, which, l)
+    pend = g.integers(0, m.vocab, B).astype(np.int32)
+    pend[probes] = orc.pending
+    eng.set_state(kv_len=lens, pending=pend, n_new=np.ones(B, np.int32))
+    draft = torch.from_numpy(g.integers(0, m.vocab, (B, k)).astype(np.int32)).cuda()
+    draft[probes] = torch.from_numpy(draft_o).cuda()
+
+    lg_o, lg_ref = orc.verify_step(k, draft_o), ref.verify_step(k, draft_o)
+    got = to_np(eng.sf_verify_step(k, draft)[probes])
+    assert rel_err(got, lg_ref) < BF16_TOL
+    assert rel_err(got, lg_o) < BF16_TOL
+    # the block's K/V rows landed in the probes' own caches, at their own positions
+    for l in range(m.n_layers):
+        kg = to_np(eng.sf_kv_export("tk", l))[probes]
+        vg = to_np(eng.sf_kv_export("tv", l))[probes]
+        for i, b in enumerate(probes):
+            rows = slice(int(lens[b]), int(lens[b]) + k + 1)
+            assert rel_err(kg[i][:, rows], orc.tk[l][i][:, rows]) < BF16_TOL
+            assert rel_err(vg[i][:, rows], orc.tv[l][i][:, rows]) < BF16_TOL
+            np.testing.assert_array_equal(kg[i][:, :rows.start], orc.tk[l][i][:, :rows.start])
+
+
 # ---- property at full size: speculative decoding emits exactly the plain-greedy stream -------------------
 def test_1b_full_size_lossless_under_graph_replay():
     from paper_2511_20340_amd.engine import random_device_weights
