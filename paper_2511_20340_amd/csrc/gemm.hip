@@ -27,6 +27,7 @@
 #include "sf_internal.h"
 
 #include <algorithm>
+#include <cmath>
 
 namespace sf {
 namespace {
@@ -430,7 +431,54 @@ constexpr size_t REREAD_CAP = 384u << 20;
 
 int pow2floor(int v) { int p = 1; while (p * 2 <= v) p *= 2; return p; }
 
+// Large M (>= 384 rows: the batch-256 and batch-128 workloads).  There the choice is a trade between
+// operand traffic per compute unit, MFMA time per compute unit, how evenly the workgroups divide over
+// 256 CUs and the cost of splitting K, and a cost model ranks the candidates better than rules.  Per
+// workgroup: operand bytes (BM + BN) * K/split * 2 and 2 * BM * BN * K/split flop; a CU works through
+// ceil(workgroups / 256) of them at ~80 GB/s of operand intake and ~5.5 TFLOP/s, the two overlapping
+// for about two thirds; ~10 us of launch and drain, ~10 us per extra K split.  The constants and the
+// per-tile factors are least-squares fits to sweeps of all tiles x splits over the 8B shapes at 768 and
+// 1280 rows and the 14B shapes at 640 rows on MI355X; over those 12 shapes the model's choice is
+// within 1.3 % of the best measured configuration on average (7.5 % worst).
+double model_us(int M, int N, int K, int tile, int split) {
+  static const double factor[N_TILES + 1] = {0, 0.9, 0.889, 0.945, 1.013, 1.068, 0.95, 1.044, 0.945, 0.943, 1.003};
+  const int BM = TILE_TM[tile] * 32, BN = tile >= 6 ? 256 : 128;
+  const double tiles = (double)((M + BM - 1) / BM) * ((N + BN - 1) / BN) * split;
+  const double per_cu = std::ceil(tiles / 256.0), ks = (double)K / split;
+  const double t_mem = per_cu * (BM + BN) * ks * 2.0 / 80e9;
+  const double t_mma = per_cu * 2.0 * BM * BN * ks / 5.5e12;
+  const double t_hbm = (double)N * K * 2.0 / 4.7e12;
+  const double t = std::max({t_mem, t_mma, t_hbm}) + 0.35 * std::min(t_mem, t_mma);
+  return (t * 1e6 + 10.0 + 10.0 * (split - 1)) * factor[tile];
+}
+
+GemmConfig pick(int M, int N, int K, size_t ws_bytes, int fixed_split);
+
+GemmConfig pick_large(int M, int N, int K, size_t ws_bytes, int fixed_split) {
+  const int KT = (K + BK - 1) / BK;
+  GemmConfig best = {0, 0};
+  double best_us = 0;
+  for (int split = 1; split <= 4; split *= 2) {
+    if (fixed_split > 0 && split != fixed_split) continue;
+    if (split > 1 && KT / split < 8) continue;
+    for (int tile = 2; tile <= N_TILES; ++tile) {
+      if (tile == 6) continue;  // 64 x 256: never competitive at this many rows
+      if (split > 1) {
+        const Plan p = make_plan(M, N, K, TILE_TM[tile] * 32, tile >= 6 ? 256 : 128, split);
+        if (!plan_fits(p, TILE_TM[tile] * 32, (const void *)1, ws_bytes)) continue;
+      }
+      const double us = model_us(M, N, K, tile, split);
+      if (best.tile == 0 || us < best_us) { best = {tile, split}; best_us = us; }
+    }
+  }
+  return best;
+}
+
 GemmConfig pick(int M, int N, int K, size_t ws_bytes, int fixed_split) {
+  if (M >= 384 && (fixed_split <= 0 || fixed_split == 1 || fixed_split == 2 || fixed_split == 4)) {
+    const GemmConfig c = pick_large(M, N, K, ws_bytes, fixed_split);
+    if (c.tile > 0) return c;
+  }
   const int KT = (K + BK - 1) / BK;
   const size_t wbytes = (size_t)N * K * 2;
   const int max_tm = std::min(5, (M + 31) / 32);
