@@ -35,6 +35,9 @@ def test_split_is_the_same_for_every_row_count_up_to_the_plan(plan):
 def test_split_needs_workspace_and_long_k():
     for N, K in SHAPES:
         assert config(160, 160, N, K, ws=0)[1] == 1          # nowhere to put partial tiles
+        assert config(640, 640, N, K, ws=0)[1] == 1
+        t, s, _ = config(1280, 1280, N, K)
+        assert s == 1 or ((K + 63) // 64) // s >= 8
         t, s, _ = config(160, 160, N, K)
         kt = (K + 63) // 64
         assert s == 1 or kt // s >= 8                        # at least 8 K slices per workgroup
