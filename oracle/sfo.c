@@ -32,11 +32,12 @@ static void round_buf(double *x, long n, int on) {
 /* y = RMSNorm(x; g) . w^T for the norm + linear pairs of the decoder layers.  Exact mode: the two
  * definitions one after the other.  bf16 emulation: the path under test stores neither the normalised
  * rows nor the gains separately -- the gain vector is folded into the weight's columns once (rounded
- * to bf16), the matrix product runs on the raw rows, and the row factor 1/sqrt(mean(x^2)+eps), which
- * commutes with the sum over the features, is applied unrounded -- so the emulation rounds w*g and
- * nothing else. */
-static void norm_linear(const double *x, const float *g, const float *w, int M, int K, int N, double eps, int on,
-                        double *y) {
+ * to bf16), the matrix product runs on the raw rows as a bf16 pipeline sees them (each element rounded
+ * to bf16: the residual stream itself is kept wider, see sfo.h), and the row factor
+ * 1/sqrt(mean(x^2)+eps), taken from the unrounded row, commutes with the sum over the features and is
+ * applied unrounded -- so the emulation rounds w*g and the product's copy of x, and nothing else. */
+void sfo_norm_linear(const double *x, const float *g, const float *w, int M, int K, int N, double eps, int on,
+                     double *y) {
   if (!on) {
     double *a = (double *)malloc(sizeof(double) * (size_t)M * K);
     sfo_rmsnorm(x, g, M, K, eps, a);
@@ -45,10 +46,13 @@ static void norm_linear(const double *x, const float *g, const float *w, int M, 
     return;
   }
   float *wf = (float *)malloc(sizeof(float) * (size_t)N * K);
+  double *xr = (double *)malloc(sizeof(double) * (size_t)M * K);
   for (long n = 0; n < N; ++n)
     for (int k = 0; k < K; ++k) wf[n * K + k] = (float)sfo_round_bf16((double)w[n * K + k] * (double)g[k]);
-  sfo_linear(x, wf, NULL, M, K, N, y);
+  for (long i = 0; i < (long)M * K; ++i) xr[i] = sfo_round_bf16(x[i]);
+  sfo_linear(xr, wf, NULL, M, K, N, y);
   free(wf);
+  free(xr);
   for (int r = 0; r < M; ++r) {
     double ss = 0.0;
     for (int e = 0; e < K; ++e) ss += x[(long)r * K + e] * x[(long)r * K + e];
@@ -183,11 +187,11 @@ static void attn_half(const sfo_cfg *c, const float *norm_g, const float *wqkv, 
                       double *kc, double *vc, int mode) {
   int d = c->d_model, Hq = c->n_q_heads, Hkv = c->n_kv_heads, hd = c->head_dim;
   int M = B * nq, NQ = Hq * hd, NKV = Hkv * hd, N = NQ + 2 * NKV, R = c->round_bf16;
-  double *a = dalloc((long)M * d), *qkv = dalloc((long)M * N);
+  double *qkv = dalloc((long)M * N);
   double *q = dalloc((long)M * NQ), *kk = dalloc((long)M * NKV), *o = dalloc((long)M * NQ);
   double *proj = dalloc((long)M * d);
   int32_t *pos = (int32_t *)malloc(sizeof(int32_t) * (size_t)M);
-  norm_linear(h, norm_g, wqkv, M, d, N, c->rms_eps, R, qkv);
+  sfo_norm_linear(h, norm_g, wqkv, M, d, N, c->rms_eps, R, qkv);
   round_buf(qkv, (long)M * N, R);
   for (int b = 0; b < B; ++b)
     for (int i = 0; i < nq; ++i) pos[b * nq + i] = len[b] + i;
@@ -211,25 +215,23 @@ static void attn_half(const sfo_cfg *c, const float *norm_g, const float *wqkv, 
   sfo_attention(q, kc, vc, len, B, nq, Hq, Hkv, hd, cap, mode, o);
   round_buf(o, (long)M * NQ, R);
   sfo_linear(o, wo, NULL, M, NQ, d, proj);
-  for (long i = 0; i < (long)M * d; ++i) h[i] += proj[i];
-  round_buf(h, (long)M * d, R);
-  free(a); free(qkv); free(q); free(kk); free(o); free(proj); free(pos);
+  for (long i = 0; i < (long)M * d; ++i) h[i] += proj[i]; /* the residual stream stays unrounded */
+  free(qkv); free(q); free(kk); free(o); free(proj); free(pos);
 }
 
 /* h += W_down( silu(W_gate n) * (W_up n) ), n = RMS(h)   (SwiGLU feed-forward, pre-norm residual) */
 static void ffn_half(const sfo_cfg *c, const float *norm_g, const float *wg, const float *wu,
                      const float *wd, double *h, int M) {
   int d = c->d_model, F = c->d_ffn, R = c->round_bf16;
-  double *a = dalloc((long)M * d), *g = dalloc((long)M * F), *u = dalloc((long)M * F);
+  double *g = dalloc((long)M * F), *u = dalloc((long)M * F);
   double *proj = dalloc((long)M * d);
-  norm_linear(h, norm_g, wg, M, d, F, c->rms_eps, R, g);
-  norm_linear(h, norm_g, wu, M, d, F, c->rms_eps, R, u);
+  sfo_norm_linear(h, norm_g, wg, M, d, F, c->rms_eps, R, g);
+  sfo_norm_linear(h, norm_g, wu, M, d, F, c->rms_eps, R, u);
   sfo_silu_mul(g, u, (long)M * F, g);
   round_buf(g, (long)M * F, R);
   sfo_linear(g, wd, NULL, M, F, d, proj);
-  for (long i = 0; i < (long)M * d; ++i) h[i] += proj[i];
-  round_buf(h, (long)M * d, R);
-  free(a); free(g); free(u); free(proj);
+  for (long i = 0; i < (long)M * d; ++i) h[i] += proj[i]; /* the residual stream stays unrounded */
+  free(g); free(u); free(proj);
 }
 
 /* Multi-token verification (Introduction, step 2): the unmodified target decoder runs over
@@ -256,9 +258,11 @@ int sfo_verify_step(const sfo_cfg *c, const sfo_target_weights *w, sfo_state *s,
     for (int g = 0; g < 4; ++g)
       if (hook_layer[g] == l)
         for (int b = 0; b < B; ++b)
-          for (int i = 0; i < nq; ++i)
-            memcpy(s->hooks + (((long)b * s->q_max + i) * 4 + g) * d, h + ((long)b * nq + i) * d,
-                   sizeof(double) * d);
+          for (int i = 0; i < nq; ++i) {
+            double *dst = s->hooks + (((long)b * s->q_max + i) * 4 + g) * d;
+            memcpy(dst, h + ((long)b * nq + i) * d, sizeof(double) * d);
+            round_buf(dst, d, c->round_bf16); /* the hooked copies are stored in the model dtype */
+          }
     if (l == L) break;
     attn_half(c, w->attn_norm[l], w->wqkv[l], w->wo[l], h, B, nq, s->kv_len, s->cap,
               s->tk + l * cache_l, s->tv + l * cache_l, SFO_MASK_CAUSAL);
@@ -310,14 +314,14 @@ int sfo_draft_step(const sfo_cfg *c, const sfo_draft_weights *w, const float *lm
       for (int e = 0; e < d; ++e) xlast[(long)b * d + e] = 0.0;
       continue;
     }
-    double *f = dalloc((long)n * 4 * d), *x = dalloc((long)n * d), *a = dalloc((long)n * d);
+    double *f = dalloc((long)n * 4 * d), *x = dalloc((long)n * d);
     double *qkv = dalloc((long)n * N), *kk = dalloc((long)n * NKV);
     int32_t *pos = (int32_t *)malloc(sizeof(int32_t) * (size_t)n);
     sfo_group_rmsnorm(s->hooks + (long)b * s->q_max * 4 * d, w->group_norm, n, 4, d, c->rms_eps, f);
     round_buf(f, (long)n * 4 * d, R);
     sfo_linear(f, w->w_ds, NULL, n, 4 * d, d, x);
     round_buf(x, (long)n * d, R);
-    norm_linear(x, w->attn_norm, w->wqkv, n, d, N, c->rms_eps, R, qkv);
+    sfo_norm_linear(x, w->attn_norm, w->wqkv, n, d, N, c->rms_eps, R, qkv);
     round_buf(qkv, (long)n * N, R);
     for (int r = 0; r < n; ++r) {
       pos[r] = s->kv_len[b] - n + r;
@@ -344,11 +348,10 @@ int sfo_draft_step(const sfo_cfg *c, const sfo_draft_weights *w, const float *lm
                     hd, cap, SFO_MASK_CAUSAL, o);
       round_buf(o, NQ, R);
       sfo_linear(o, w->wo, NULL, 1, NQ, d, proj);
-      for (int e = 0; e < d; ++e) xlast[(long)b * d + e] += proj[e];
-      round_buf(xlast + (long)b * d, d, R);
+      for (int e = 0; e < d; ++e) xlast[(long)b * d + e] += proj[e]; /* residual stream: unrounded */
       free(q); free(o); free(proj);
     }
-    free(f); free(x); free(a); free(qkv); free(kk); free(pos);
+    free(f); free(x); free(qkv); free(kk); free(pos);
   }
   /* step 3 */
   int M = B * k;
@@ -356,7 +359,7 @@ int sfo_draft_step(const sfo_cfg *c, const sfo_draft_weights *w, const float *lm
   sfo_rmsnorm(xlast, w->pos_norm, B, d, c->rms_eps, an);
   round_buf(an, (long)B * d, R);
   sfo_linear(an, w->w_pos, w->b_pos, B, d, k * d, S); /* row b = [slot0 | slot1 | ...] = rows b*k+s of S */
-  round_buf(S, (long)M * d, R);
+  /* S is the residual stream of the slot layer: unrounded */
   /* step 4 */
   if (two_stage) {
     /* the slots alone: an empty prefix in a k-slot cache of their own */
@@ -383,32 +386,41 @@ int sfo_draft_step(const sfo_cfg *c, const sfo_draft_weights *w, const float *lm
 /* Multi-token acceptance (Introduction, step 3; lossless condition 1): a draft token is
  * accepted only while it equals the target's own greedy choice; the first disagreement
  * (or the row after the last slot) contributes the target's token as a bonus, so
- * 1 <= a_b <= k+1.  The K/V of the accepted rows already sit behind the prefix, so the
- * commit is kv_len += a_b.  force_len (prefill) commits a fixed number of rows instead;
- * the pending token is then the target's choice after the last committed row. */
+ * 1 <= a_b <= k+1.  Written as the definition reads: slot i counts when it and every slot
+ * before it agree with the target, i.e. n_b = sum_i prod_{j<=i} [draft_j == p_j].  The K/V of
+ * the accepted rows already sit behind the prefix, so the commit is kv_len += a_b.  force_len
+ * (prefill) commits a fixed number of rows instead; the pending token is then the target's
+ * choice after the last committed row.  cu_new is the exclusive prefix sum of the a_b. */
 int sfo_accept_commit(sfo_state *s, int k, int V, const int32_t *draft, const double *logits,
                       const int32_t *force_len, int32_t *accept_len, int32_t *out_tokens) {
   int B = s->B, nq = k + 1;
-  s->cu_new[0] = 0;
+  if (nq > 64) return -1;
+  if (force_len)
+    for (int b = 0; b < B; ++b)
+      if (force_len[b] < 0 || force_len[b] > nq) return -1;
+  /* the target's greedy choice at every block row */
+  int32_t *p = (int32_t *)malloc(sizeof(int32_t) * (size_t)B * nq);
+  for (long r = 0; r < (long)B * nq; ++r) p[r] = sfo_argmax(logits + r * V, V);
+  /* accept lengths */
   for (int b = 0; b < B; ++b) {
-    int32_t p[64];
-    if (nq > 64) return -1;
-    for (int i = 0; i < nq; ++i) p[i] = sfo_argmax(logits + ((long)b * nq + i) * V, V);
-    int a;
-    if (force_len) {
-      a = force_len[b];
-      if (a < 0 || a > nq) return -1;
-    } else {
-      int n = 0;
-      while (n < k && draft[b * k + n] == p[n]) ++n;
-      a = n + 1;
+    if (force_len) { accept_len[b] = force_len[b]; continue; }
+    int agree_so_far = 1, n = 0;
+    for (int i = 0; i < k; ++i) {
+      agree_so_far *= (draft[b * k + i] == p[b * nq + i]);
+      n += agree_so_far;
     }
-    for (int i = 0; i < nq; ++i) out_tokens[b * nq + i] = i < a ? p[i] : -1;
-    accept_len[b] = a;
-    if (a > 0) s->pending[b] = p[a - 1];
+    accept_len[b] = n + 1;
+  }
+  /* emitted tokens, commit */
+  for (int b = 0; b < B; ++b) {
+    int a = accept_len[b];
+    for (int i = 0; i < nq; ++i) out_tokens[b * nq + i] = i < a ? p[b * nq + i] : -1;
+    if (a > 0) s->pending[b] = p[b * nq + a - 1];
     s->kv_len[b] += a;
     s->n_new[b] = a;
-    s->cu_new[b + 1] = s->cu_new[b] + a;
   }
+  s->cu_new[0] = 0;
+  for (int b = 0; b < B; ++b) s->cu_new[b + 1] = s->cu_new[b] + accept_len[b];
+  free(p);
   return 0;
 }

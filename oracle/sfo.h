@@ -10,8 +10,13 @@
  * Arithmetic: every floating-point operation is IEEE double.  Weights are
  * passed as float arrays (they hold bf16- or fp32-representable values),
  * activations, caches and logits as double arrays.  With cfg.round_bf16 != 0
- * the tensors that a bf16 pipeline stores to memory are rounded to bf16
+ * the tensors that a bf16 pipeline stores to memory in bf16 are rounded to bf16
  * (round-to-nearest-even) at exactly those points; accumulation stays double.
+ * The residual stream of the decoder layers (the running sum h that every
+ * attention and feed-forward block adds to, and the slot states of the draft
+ * block) is NOT among them: a bf16 pipeline keeps that one sum in a wider type,
+ * so it is left unrounded here; what is read from it is rounded where it is
+ * consumed (the hooked copies, the operand of a matrix product, a norm's output).
  *
  * Pins (tests/test_oracle_*.py): brute-force softmax attention on tiny shapes,
  * k=1 hybrid mask == causal decode, block-causal rows == successive decodes,
@@ -94,6 +99,9 @@ double sfo_round_bf16(double x);
 void sfo_rmsnorm(const double *x, const float *g, int M, int d, double eps, double *y);
 void sfo_group_rmsnorm(const double *x, const float *g, int M, int ng, int d, double eps, double *y);
 void sfo_linear(const double *x, const float *w, const float *bias, int M, int K, int N, double *y);
+/* RMSNorm(x; g) . w^T; round_bf16 != 0: as a bf16 pipeline that folds g into w computes it (sfo.c) */
+void sfo_norm_linear(const double *x, const float *g, const float *w, int M, int K, int N, double eps,
+                     int round_bf16, double *y);
 void sfo_rope(double *x, const int32_t *pos, int M, int H, int hd, double theta);
 void sfo_silu_mul(const double *gate, const double *up, long n, double *y);
 void sfo_attention(const double *q, const double *kc, const double *vc, const int32_t *len,

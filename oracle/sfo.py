@@ -118,6 +118,17 @@ def linear(x, w, bias=None):
     return y
 
 
+def norm_linear(x, g, w, eps=1e-6, round_bf16=False):
+    """RMSNorm(x; g) . w^T as the decoder layers' norm + linear pairs compute it."""
+    x, g, w = _c64(x), _c32(g), _c32(w)
+    M, K = x.shape
+    N = w.shape[0]
+    assert w.shape == (N, K) and g.shape == (K,)
+    y = np.empty((M, N))
+    lib().sfo_norm_linear(_dp(x), _fp(g), _fp(w), M, K, N, C.c_double(eps), int(bool(round_bf16)), _dp(y))
+    return y
+
+
 def rope(x, pos, theta=10000.0):
     x = _c64(x).copy()
     pos = np.ascontiguousarray(pos, dtype=np.int32)

@@ -361,3 +361,32 @@ def test_lossless_speculative_equals_plain_greedy(rb):
             assert np.all(accs == want_acc)
         if fn is partly:
             assert np.all(accs[:, 0] == 2) and np.all(accs[:, 1] == k + 1) and np.all(accs[:, 2] == 3)
+
+
+def test_round_bf16_mode_stays_close_to_exact_mode_and_rounds_what_is_stored():
+    """The rounding emulation moves the pin model's logits by well under the bf16 tolerance of the
+    GPU parity tests, stores bf16 values in hooks and caches, and leaves the residual stream wider:
+    HS[L] as hooked is the bf16 rounding of a row that is itself not bf16-representable (the final
+    logits depend on the unrounded row)."""
+    tw, dw = weights(0.1)
+    tw = {n: ([synth.to_bf16_values(a) for a in v] if isinstance(v, list) else synth.to_bf16_values(v))
+          for n, v in tw.items()}
+    prompts = synth.prompts([9, 6], SHAPE.vocab, 12)
+    k = 3
+    draft = np.random.default_rng(3).integers(0, SHAPE.vocab, (2, k)).astype(np.int32)
+    lg = {}
+    for rb in (False, True):
+        o = new_oracle(tw, dw, 2, rb=rb)
+        o.prefill(prompts)
+        lg[rb] = o.verify_step(k, draft)
+        if rb:
+            hk = o.hooks[:, :k + 1]
+            np.testing.assert_array_equal(hk, synth.to_bf16_values(hk.astype(np.float32)))
+            n = int(o.kv_len.min())
+            np.testing.assert_array_equal(o.tk[:, :, :, :n], synth.to_bf16_values(o.tk[:, :, :, :n].astype(np.float32)))
+            # logits from the rounded hook HS[L] differ from the real ones: the stream itself is not rounded
+            a = sfo.rmsnorm(hk[:, :, 3], tw["final_norm"], SHAPE.rms_eps)
+            from_hook = sfo.linear(synth.to_bf16_values(a.astype(np.float32)).astype(np.float64), tw["lm_head"])
+            assert not np.array_equal(from_hook.astype(np.float32), lg[True].astype(np.float32))
+    err = np.abs(lg[True] - lg[False]).max() / np.abs(lg[False]).max()
+    assert 0 < err < 1e-2, err

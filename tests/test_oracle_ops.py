@@ -128,3 +128,53 @@ def test_argmax_ties_and_nan():
     assert sfo.argmax(np.array([np.nan, 1.0, np.nan, 1.0])) == 1    # NaN never wins
     assert sfo.argmax(np.array([-np.inf, -np.inf])) == 0
     assert sfo.argmax(np.array([-5.0, -2.0, -9.0])) == 1
+
+
+# ---- the norm + linear pair, exact and as a bf16 pipeline computes it ---------------------------------
+def _bf16(a):
+    """bf16 rounding through torch's cast (an implementation other than the oracle's)."""
+    return torch.from_numpy(np.asarray(a, np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+
+
+def test_norm_linear_exact_mode_is_norm_then_linear():
+    rs = np.random.default_rng(3)
+    x = rs.standard_normal((5, 24)); g = rs.uniform(0.5, 1.5, 24).astype(np.float32)
+    w = rs.standard_normal((7, 24)).astype(np.float32)
+    want = (x / np.sqrt((x * x).mean(-1, keepdims=True) + 1e-6) * g) @ w.astype(np.float64).T
+    np.testing.assert_allclose(sfo.norm_linear(x, g, w), want, rtol=1e-12, atol=1e-12)
+
+
+def test_norm_linear_bf16_mode_rounding_points():
+    """round_bf16 mode: the gains are folded into the weight (w*g rounded to bf16 once), the product
+    runs on the bf16 copy of the raw row, the row factor comes from the unrounded row and is applied
+    unrounded.  Pinned against a numpy composition with torch's bf16 cast."""
+    rs = np.random.default_rng(4)
+    M, K, N = 6, 40, 9
+    x = rs.standard_normal((M, K)) * 3.0                       # fp32-like values, not bf16-representable
+    w = _bf16(rs.standard_normal((N, K)) * 0.05).astype(np.float32)
+    for g in (np.ones(K, np.float32), _bf16(rs.uniform(0.25, 2.0, K)).astype(np.float32)):
+        rinv = 1.0 / np.sqrt((x * x).mean(-1, keepdims=True) + 1e-6)
+        want = (_bf16(x) @ _bf16(w.astype(np.float64) * g).T) * rinv
+        got = sfo.norm_linear(x, g, w, round_bf16=True)
+        np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
+    # unit gains and bf16-valued rows: the emulation rounds nothing at all -> equals the exact mode
+    xb = _bf16(x)
+    np.testing.assert_allclose(sfo.norm_linear(xb, np.ones(K, np.float32), w, round_bf16=True),
+                               sfo.norm_linear(xb, np.ones(K, np.float32), w), rtol=1e-12, atol=1e-13)
+
+
+def test_norm_linear_bf16_mode_stays_within_the_rounding_bound_of_exact():
+    """Each product x_k * (w g)_k is perturbed by two bf16 roundings (unit roundoff u = 2^-8), so
+    |y_rb - y_exact| <= ((1+u)^2 - 1) * rinv * sum_k |x_k w_k g_k|, element by element."""
+    rs = np.random.default_rng(5)
+    M, K, N = 8, 96, 12
+    x = rs.standard_normal((M, K)) * 0.7
+    g = rs.uniform(0.25, 2.0, K).astype(np.float32)
+    w = (rs.standard_normal((N, K)) * 0.05).astype(np.float32)
+    exact = sfo.norm_linear(x, g, w)
+    got = sfo.norm_linear(x, g, w, round_bf16=True)
+    u = 2.0 ** -8
+    rinv = 1.0 / np.sqrt((x * x).mean(-1, keepdims=True) + 1e-6)
+    bound = ((1 + u) ** 2 - 1) * (np.abs(x) @ np.abs(w.astype(np.float64) * g).T) * rinv
+    assert np.all(np.abs(got - exact) <= bound * (1 + 1e-9))
+    assert np.abs(got - exact).max() > 0                       # and the rounding really happens
