@@ -23,6 +23,7 @@ HBM_PEAK = 8.0e12
 MFMA_BF16_PEAK = 2.5e15
 FP32_PEAK = 157.3e12
 # kappa (mean tokens per target call) of the paper's model-size table at k=4 / k=2, by model class
+DEFAULT_CONFIG = 4
 PAPER_KAPPA = {"1b-bf16": 1.84, "8b-bf16": 1.75, "14b-bf16": 1.71, "tiny-f32": 1.84}
 
 
@@ -39,63 +40,101 @@ def solve_alpha(kappa, k):
 
 
 def gemm_shapes(m, B, k, qm, two_stage=False):
-    """(M, N, K, out_bytes_per_elem, has_residual) of every linear launch in one step."""
+    """One dict per linear launch of a step: rows M, output features N, reduction K, and the bytes the launch
+    must write (`out_bytes`) and read besides weights and input rows (`res_bytes`).  bf16 mode: the residual
+    stream is float (read 4 + written 4 bytes per element) with a bf16 copy for the next matrix product (2
+    more); gate/up leave M x F gated activations, never the 2F pre-activations; the LM heads leave one token
+    id per row (their logits are reduced inside the kernel)."""
     es = 2 if m.dtype == "bf16" else 4
+    stream_out = 4 + (2 if m.dtype == "bf16" else 0)
     d, F, V = m.d_model, m.d_ffn, m.vocab
     nq, nkv = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim
     M, Mh, Ms = B * (k + 1), B * qm, B * k
-    layer = lambda rows: [(rows, nq + 2 * nkv, d, es, 0), (rows, d, nq, es, 1), (rows, 2 * F, d, 4, 0),
-                          (rows, d, F, es, 1)]
-    out = layer(M) * m.n_layers + [(M, V, d, 4, 0)]
+
+    def lin(rows, N, K, out_bytes, res_bytes=0):
+        return {"M": rows, "N": N, "K": K, "out_bytes": out_bytes, "res_bytes": res_bytes}
+
+    def layer(rows, last_copy=True):
+        return [lin(rows, nq + 2 * nkv, d, rows * (nq + 2 * nkv) * es),
+                lin(rows, d, nq, rows * d * stream_out, rows * d * 4),
+                lin(rows, 2 * F, d, rows * F * es),
+                lin(rows, d, F, rows * d * (stream_out if last_copy else 4), rows * d * 4)]
+
+    def head(rows):
+        return lin(rows, V, d, rows * 4 if m.dtype == "bf16" else rows * V * 4)
+    out = layer(M) * m.n_layers + [head(M)]
     if k > 0:
-        out += [(Mh, d, 4 * d, es, 0), (Mh, 2 * nkv, d, es, 0), (B, k * d, d, es, 0)] + layer(Ms) + [(Ms, V, d, 4, 0)]
+        out += [lin(Mh, d, 4 * d, Mh * d * es), lin(Mh, 2 * nkv, d, Mh * 2 * nkv * es),
+                lin(B, k * d, d, Ms * d * stream_out)] + layer(Ms, last_copy=False) + [head(Ms)]
         if two_stage:   # query and output projection of the context attention's newest row
-            out += [(B, nq, d, es, 0), (B, d, nq, es, 1)]
+            out += [lin(B, nq, d, B * nq * es), lin(B, d, nq, B * d * 4, B * d * es)]
     return out
 
 
 def gemm_work(shapes, es):
-    by = sum(K * N * es + M * K * es + M * N * ob + (M * N * es if res else 0) for M, N, K, ob, res in shapes)
-    fl = sum(2.0 * M * N * K for M, N, K, _, _ in shapes)
+    by = sum(s["K"] * s["N"] * es + s["M"] * s["K"] * es + s["out_bytes"] + s["res_bytes"] for s in shapes)
+    fl = sum(2.0 * s["M"] * s["N"] * s["K"] for s in shapes)
     return by, fl
 
 
 def cpu_baseline(wl, seed, budget_s=25.0):
-    """The oracle, as it stands, on a bounded sample: B' = 2 sequences of the same model at the
-    workload's prefix length, seeded caches, natural drafts; whole steps (draft + verify + accept)."""
+    """The oracle, as it stands, on a bounded sample: B' = 2 sequences of the same model at the workload's
+    mean prefix length, seeded caches, natural drafts; whole steps (draft + verify + accept).  Models whose
+    weights would take minutes to draw and tens of GB to hold on the host are sampled in depth too: whole
+    steps at L' = 1 and L' = 4 target layers (same widths, same heads), extrapolated linearly to L layers --
+    every layer costs the same, the draft block and the two LM heads are in both measurements."""
     import synth
     from oracle import sfo
     m, k = wl.model, wl.k
     Bp = min(2, wl.batch)
     prefix = int((wl.prefix_lo + wl.prefix_hi) // 2)
     cap = synth.kv_capacity(prefix, 4, k)
+    per_layer = m.d_model * ((m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim + m.n_q_heads * m.head_dim + 3 * m.d_ffn)
+    full_depth = m.n_layers * per_layer < 1.5e9
+    depths = [m.n_layers] if full_depth else [1, 4]
     t0 = time.time()
-    tw = synth.target_weights(m, seed)
-    dw = synth.draft_weights(m, k, seed)
-    orc = sfo.Oracle(m.cfg(), tw, dw, Bp, cap, q_max=k + 1)
-    g = synth.rng(seed, 777)
-    for name in ("tk", "tv", "dk", "dv"):
-        getattr(orc, name)[...] = g.standard_normal(getattr(orc, name).shape, dtype=np.float32)
-    orc.hooks[...] = g.standard_normal(orc.hooks.shape, dtype=np.float32)
-    orc.kv_len[:] = prefix
-    orc.n_new[:] = 1
-    orc.pending[:] = g.integers(0, m.vocab, Bp)
+    tw_d, dw_d = synth.device_weights(m.scaled(n_layers=depths[-1]), k, seed)
+    tw, dw = synth.host_weights(tw_d, dw_d)
+    del tw_d, dw_d
     setup = time.time() - t0
-    steps, tokens, t_used = 0, 0, 0.0
-    while steps < 1 or (t_used < budget_s and steps < 4 and t_used / steps * (steps + 1) < budget_s):
-        t1 = time.time()
-        d = orc.draft_step(k)
-        lg = orc.verify_step(k, d)
-        acc, _ = orc.accept_commit(k, d, lg)
-        t_used += time.time() - t1
-        tokens += int(acc.sum())
-        steps += 1
-    return {"value": tokens / t_used, "unit": "accepted tokens/s", "cores": sfo.ncores(), "kind": "oracle",
-            "sample": f"{steps} whole step(s) (draft+verify+accept) at B'={Bp} of {wl.batch}, all {m.n_layers} layers, "
-                      f"prefix {prefix}, k={k}, seeded caches, natural drafts; fp64 naive C + OpenMP; "
-                      f"{t_used:.1f}s timed, {setup:.1f}s setup; per-sequence cost is batch-independent",
-            "ms_per_step_sample": 1e3 * t_used / steps}
 
+    def run(depth, budget):
+        mm = m.scaled(n_layers=depth)
+        twd = {n: (v[:depth] if isinstance(v, list) else v) for n, v in tw.items()}
+        orc = sfo.Oracle(mm.cfg(), twd, dw, Bp, cap, q_max=k + 1)
+        g = synth.rng(seed, 777)
+        for name in ("tk", "tv", "dk", "dv"):
+            getattr(orc, name)[...] = g.standard_normal(getattr(orc, name).shape, dtype=np.float32)
+        orc.hooks[...] = g.standard_normal(orc.hooks.shape, dtype=np.float32)
+        orc.kv_len[:] = prefix
+        orc.n_new[:] = 1
+        orc.pending[:] = g.integers(0, m.vocab, Bp)
+        steps, tokens, t_used = 0, 0, 0.0
+        while steps < 1 or (t_used < budget and steps < 4 and t_used / steps * (steps + 1) < budget):
+            t1 = time.time()
+            d = orc.draft_step(k)
+            lg = orc.verify_step(k, d)
+            acc, _ = orc.accept_commit(k, d, lg)
+            t_used += time.time() - t1
+            tokens += int(acc.sum())
+            steps += 1
+        return t_used / steps, tokens / steps, steps, t_used
+    runs = [run(depth, budget_s / len(depths)) for depth in depths]
+    if full_depth:
+        t_step, tok_step = runs[0][0], runs[0][1]
+        how = f"{runs[0][2]} whole step(s) at all {m.n_layers} layers"
+    else:
+        slope = (runs[1][0] - runs[0][0]) / (depths[1] - depths[0])
+        t_step = runs[0][0] + slope * (m.n_layers - depths[0])
+        tok_step = runs[1][1]
+        how = (f"whole steps at L'={depths[0]} ({runs[0][2]} steps, {1e3 * runs[0][0]:.0f} ms each) and L'={depths[1]} "
+               f"({runs[1][2]} steps, {1e3 * runs[1][0]:.0f} ms each) of {m.n_layers} target layers at the real widths, "
+               f"extrapolated linearly in depth")
+    return {"value": tok_step / t_step, "unit": "accepted tokens/s", "cores": sfo.ncores(), "kind": "oracle",
+            "sample": f"draft+verify+accept at B'={Bp} of {wl.batch} sequences, prefix {prefix}, k={k}, seeded caches, "
+                      f"natural drafts; {how}; fp64 naive C + OpenMP; {sum(r[3] for r in runs):.1f}s timed, "
+                      f"{setup:.1f}s weight setup; per-sequence cost is batch-independent",
+            "ms_per_step_sample": 1e3 * t_step}
 
 
 def stream_copy_rate(torch, sfb):
@@ -136,7 +175,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=1, help="index into the baseline's configs (default 1: 1B bf16)")
+    ap.add_argument("--config", type=int, default=DEFAULT_CONFIG,
+                    help="index into the baseline's configs (default: the 14B-shaped batch-128 workload)")
     ap.add_argument("--k", type=int, default=None)
     ap.add_argument("--draft-wiring", choices=["hybrid", "two-stage"], default="hybrid",
                     help="hybrid: one draft attention over cached context + slots (default); two-stage: context "
@@ -162,7 +202,7 @@ def main():
 
     import torch
     import synth
-    from paper_2511_20340_amd.engine import Engine, random_device_weights
+    from paper_2511_20340_amd.engine import Engine
     from paper_2511_20340_amd import binding as sfb
 
     wl = synth.WORKLOADS[args.config]
@@ -173,8 +213,6 @@ def main():
     es = 2 if m.dtype == "bf16" else 4
     torch.cuda.set_device(0)
 
-    if args.attn_chunk:
-        sfb.check(sfb.lib().sf_tune_attention(args.attn_chunk), "sf_tune_attention")
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -190,10 +228,12 @@ def main():
     total_steps = n_pass * (steps + warm) + 6
     cap = synth.kv_capacity(int(lens.max()), total_steps, k)
     eng = Engine(m.cfg(), B, cap, k)
+    if args.attn_chunk:
+        eng.sf_tune_attention(args.attn_chunk)
     two_stage = args.draft_wiring == "two-stage"
     draft_mode = (sfb.SF_MASK_BIDIR if args.draft_mask == "bidir" else sfb.SF_MASK_CAUSAL) | \
         (sfb.SF_DRAFT_TWO_STAGE if two_stage else 0)
-    tw, dw = random_device_weights(m, k, wl.seed, two_stage)
+    tw, dw = synth.device_weights(m, k, wl.seed, two_stage)
     eng.bind(tw, dw)
     del tw, dw
 
@@ -220,12 +260,12 @@ def main():
     ar = torch.zeros(B, n_ar, dtype=torch.int32, device="cuda")
     ar[:, 0] = eng.pending
     none = torch.zeros(B, 0, dtype=torch.int32, device="cuda")
-    lg1 = torch.empty(B, 1, m.vocab, dtype=torch.float32, device="cuda")
+    id1 = torch.empty(B, 1, dtype=torch.int32, device="cuda")
     for j in range(1, n_ar):
         if eng.len_upper + 1 > cap or args.seeded_state:
             break
-        eng.sf_verify_step(0, none, logits_out=lg1)
-        _, out = eng.sf_accept_commit(0, none, lg1)
+        eng.sf_verify_step(0, none, ids_out=id1, logits=False)
+        _, out = eng.sf_accept_commit(0, none, id1)
         ar[:, j] = out[:, 0]
     torch.cuda.synchronize()
     for n, t in snap.items():
@@ -241,7 +281,7 @@ def main():
     slot = torch.arange(max(k, 1), device="cuda", dtype=torch.int64)[None, :k]
 
     draft = torch.zeros(B, k, dtype=torch.int32, device="cuda")
-    logits = torch.empty(B, k + 1, m.vocab, dtype=torch.float32, device="cuda")
+    tids = torch.empty(B, k + 1, dtype=torch.int32, device="cuda")     # the target's choices; logits are never stored
     toks = torch.empty(B, k + 1, dtype=torch.int32, device="cuda")
 
     n_rec = steps + warm + 2
@@ -257,8 +297,8 @@ def main():
         if calibrated and k > 0:
             idx = (eng.kv_len.to(torch.int64) - len_t + 1)[:, None] + slot
             draft.copy_(torch.gather(inj, 1, idx.clamp_(max=n_ar - 1)))
-        eng.sf_verify_step(k, draft, logits_out=logits)
-        eng.sf_accept_commit(k, draft, logits, accept_out=acc_buf, tokens_out=toks)
+        eng.sf_verify_step(k, draft, ids_out=tids, logits=False)
+        eng.sf_accept_commit(k, draft, tids, accept_out=acc_buf, tokens_out=toks)
         acc_sum.add_(acc_buf)
 
     def run_eager(n, calibrated, len_hist=None, phase_ev=None, record=False):
@@ -273,12 +313,12 @@ def main():
                 phase_ev[i][1].record()
             if len_hist is not None:
                 len_hist[i].copy_(eng.kv_len)
-            eng.sf_verify_step(k, draft, logits_out=logits)
+            eng.sf_verify_step(k, draft, ids_out=tids, logits=False)
             if phase_ev is not None:
                 phase_ev[i][2].record()
             if record:   # where in the plain-greedy stream this step's first output token belongs
                 tok_pos[hist_i[0]].copy_(eng.kv_len.to(torch.int64) - len_t + 1)
-            eng.sf_accept_commit(k, draft, logits, accept_out=acc_buf,
+            eng.sf_accept_commit(k, draft, tids, accept_out=acc_buf,
                                  tokens_out=tok_hist[hist_i[0]] if record else toks)
             acc_sum.add_(acc_buf)
             if record:
@@ -342,18 +382,18 @@ def main():
     # same packed weights, a copy of the prefilled target cache, timed over as many target calls.
     ar_ms = None
     if not args.seeded_state and k > 0:
-        eng0 = Engine(m.cfg(), B, cap, 0)
+        # it works on the same target caches: its rows land behind the prefixes, where the speculative passes
+        # that follow overwrite them (dead slots until committed)
+        eng0 = Engine(m.cfg(), B, cap, 0, share_caches=eng)
         eng0.bind_shared(eng)
-        eng0.tk.copy_(eng.tk)
-        eng0.tv.copy_(eng.tv)
         eng0.set_state(kv_len=lens, pending=snap["pending"].cpu().numpy(), n_new=np.ones(B, np.int32))
         eng0.len_upper = len0
         acc1 = torch.empty(B, dtype=torch.int32, device="cuda")
         out1 = torch.empty(B, 1, dtype=torch.int32, device="cuda")
 
         def ar_step():
-            eng0.sf_verify_step(0, none, logits_out=lg1)
-            eng0.sf_accept_commit(0, none, lg1, accept_out=acc1, tokens_out=out1)
+            eng0.sf_verify_step(0, none, ids_out=id1, logits=False)
+            eng0.sf_accept_commit(0, none, id1, accept_out=acc1, tokens_out=out1)
         if args.graph:
             eng0.pin_len_upper()
             eng0.len_upper = eng.cap - (k + 1)    # the same attention grid bound as the k-step graph
@@ -456,6 +496,7 @@ def main():
         att_bytes = float(np.mean(att_v + att_d))
         att_flops = float(np.mean(4.0 * m.n_q_heads * m.head_dim *
                                   (m.n_layers * (k + 1) * (lsum + B * (k + 1)) + k * (lsum + B * k))))
+        # fp32 mode scans stored logits; bf16 mode has no such pass (the class is then absent)
         arg_bytes = 4.0 * m.vocab * B * ((k + 1) + k)
         kernels = {}
         for name, (ms, cnt) in prof.items():
@@ -489,6 +530,9 @@ def main():
                      "algorithmic_per_launch": (e.get("bytes_per_step", 0.0) if roof["unit"] == "GB/s" else
                                                 e.get("flops_per_step", 0.0)) / e["launches_per_step"],
                      "traffic": profile_traffic(wl.name, dom),
+                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this workload, scaled by a copy "
+                                       "kernel of known size; read from the summary under profiles/ (hardware counters "
+                                       "cannot be collected from inside this process)",
                      "how": "HIP events around every launch of the class on the launch stream, same steps as the timed pass"})
         result["roofline"] = roof
 

@@ -43,7 +43,8 @@ typedef enum {
   SF_OK = 0,
   SF_EINVAL = 1,       /* null pointer, size out of range, inconsistent shapes, misaligned pointer */
   SF_ECAPACITY = 2,    /* host_len_upper + block does not fit the cache capacity / workspace      */
-  SF_ESTATE = 3,       /* call before sf_bind                                                      */
+  SF_ESTATE = 3,       /* call order: a step before sf_bind; sf_accept_commit without a preceding
+                          sf_verify_step of the same state and k (or a second commit of one block)   */
   SF_EHIP = 4,         /* a HIP call failed; see sf_last_hip_error                                 */
   SF_EUNSUPPORTED = 5  /* shape outside what the kernels cover (e.g. head_dim, rows per KV head)   */
 } sf_status;
@@ -127,7 +128,7 @@ typedef struct {
 
 /* Context.  host.  max_B <= 4096, 0 <= max_k <= 15.  target and draft must agree on every field
  * but n_layers (draft: 1).  SF_EUNSUPPORTED unless head_dim in {64,128} for SF_BF16 (any multiple
- * of 8 up to 256 for SF_F32), d_model % 8 == 0, d_ffn % 8 == 0. */
+ * of 8 up to 256 for SF_F32), d_model % 8 == 0, d_ffn % 32 == 0, (n_q_heads * head_dim) % 32 == 0. */
 sf_status sf_create(const sf_model_cfg *target, const sf_model_cfg *draft, int32_t max_B, int32_t max_k,
                     sf_ctx **out);
 sf_status sf_destroy(sf_ctx *ctx);
@@ -159,22 +160,29 @@ sf_status sf_draft_step(sf_ctx *ctx, const sf_state *st, int32_t k, int32_t mask
  * draft_tokens[b][i-1]) at position kv_len[b]+i.  Runs the target decoder over the B*(k+1) rows
  * with the CAUSAL block mask, writes the rows' K/V into the target caches at their positions
  * (rows beyond what accept later commits stay dead), writes hooks[b][i][0..3] and
- * logits: dev float [B][k+1][vocab] out.  draft_tokens: dev [B][k] (ignored when k == 0).
- * SF_ECAPACITY when host_len_upper + k + 1 > cap. */
+ * target_ids: dev [B][k+1] out, the target's greedy choice after every block row,
+ *   target_ids[b][i] = argmax_v logits[b][i][v] (lowest index on ties, NaN never wins).  In SF_BF16 mode
+ *   the arg-max is taken on the LM-head kernel's fp32 accumulators, tile by tile, so the logits need not
+ *   be stored at all;
+ * logits: dev float [B][k+1][vocab] out, or NULL when only target_ids are wanted.
+ * draft_tokens: dev [B][k] (ignored when k == 0).  SF_ECAPACITY when host_len_upper + k + 1 > cap. */
 sf_status sf_verify_step(sf_ctx *ctx, const sf_state *st, int32_t k, const int32_t *draft_tokens,
-                         int32_t host_len_upper, float *logits, void *stream);
+                         int32_t host_len_upper, float *logits, int32_t *target_ids, void *stream);
 
 /* Multi-token acceptance (lossless SD, condition 1: only draft tokens equal to the target's own
- * output are accepted).  p[b][i] = argmax_v logits[b][i][v] (lowest index on ties, NaN never wins);
+ * output are accepted).  p = target_ids (dev [B][k+1], as sf_verify_step wrote them);
  * n_b = longest prefix with draft_tokens[b][i] == p[b][i]; a_b = n_b + 1 (the target's token at
  * the first mismatch, or after the last slot, is the bonus);  out_tokens[b][i] = p[b][i] for
  * i < a_b else -1;  accept_len[b] = a_b;  pending[b] = p[b][a_b-1];  kv_len[b] += a_b;
  * n_new[b] = a_b;  cu_new = exclusive scan of a.  The accepted rows' K/V already sit behind the
  * prefix, so nothing is moved.  force_len (dev [B] or NULL): commit exactly force_len[b] in
  * [0,k+1] rows instead of matching (prefill); with 0 the sequence's pending token is kept.
- * accept_len: dev [B] out; out_tokens: dev [B][k+1] out. */
+ * accept_len: dev [B] out; out_tokens: dev [B][k+1] out.
+ * SF_ESTATE unless the last step call on this context that touched the caches was
+ * sf_verify_step(ctx, st, k, ...) with this state (identified by st->kv_len) and this k: there is
+ * nothing else to commit, and one block is committed once. */
 sf_status sf_accept_commit(sf_ctx *ctx, const sf_state *st, int32_t k, const int32_t *draft_tokens,
-                           const float *logits, const int32_t *force_len, int32_t *accept_len,
+                           const int32_t *target_ids, const int32_t *force_len, int32_t *accept_len,
                            int32_t *out_tokens, void *stream);
 
 /* Plain <-> tiled K/V layout, one layer: plain is dev elem [B][Hkv][cap][hd]; `tiled` points at
@@ -236,19 +244,15 @@ sf_status sf_op_rmsnorm_linear(const sf_ctx *ctx, const void *x, const void *w, 
  * one kernel, gate/up never leave registers; SF_F32: workspace must hold M*2F floats). act: dev elem. */
 sf_status sf_op_linear_swiglu(const sf_ctx *ctx, const void *x, const void *w_gate_up, void *act, int32_t M,
                               int32_t F, int32_t K, void *workspace, size_t workspace_bytes, void *stream);
-/* Tuning aid: force the linear kernels' tile configuration (1..sf_linear_num_tiles()) and split-K
- * factor; 0 = automatic choice.  A forced pair whose partial tiles do not fit the workspace makes the
- * launch fail with SF_EHIP.  Process-wide. host. */
-sf_status sf_tune_linear(int32_t tile, int32_t split_k);
-int32_t sf_linear_num_tiles(void);
-/* The automatic choice for a bf16 linear layer of M rows whose weight [N][K] is also used with up to
- * plan_M >= M rows: *split_k is the same for every M <= plan_M (so a row's result does not depend on
- * the rows batched with it), *tile follows M; *tile_rows = rows per workgroup of that tile.  Pure
- * host arithmetic, no GPU needed.  host pointers. */
-sf_status sf_linear_config(int32_t M, int32_t plan_M, int32_t N, int32_t K, size_t workspace_bytes,
-                           int32_t *tile, int32_t *split_k, int32_t *tile_rows);
-/* Tuning aid: force the attention's split-KV chunk size in 32-key tiles (>= 16); 0 = automatic. host. */
-sf_status sf_tune_attention(int32_t chunk_tiles);
+/* The LM head with its arg-max, as the step calls run it: ids[m] = argmax_n (x . w^T)[m][n] (lowest index
+ * on ties, NaN never wins).  SF_BF16: one linear launch whose epilogue reduces every column tile of its
+ * fp32 accumulators to (largest value, its column), then one small launch that finishes each row; logits
+ * (dev float [M][N], or NULL) are stored only when given.  SF_F32: logits are materialised (in `logits`, or
+ * in the workspace) and scanned.  x: dev elem [M][K]; w: packed [N][K]; ids: dev [M];
+ * workspace: dev, 256-byte aligned, sf_linear_argmax_workspace_bytes. */
+size_t sf_linear_argmax_workspace_bytes(const sf_ctx *ctx, int32_t M, int32_t N);
+sf_status sf_op_linear_argmax(const sf_ctx *ctx, const void *x, const void *w, int32_t M, int32_t N, int32_t K,
+                              int32_t *ids, float *logits, void *workspace, size_t workspace_bytes, void *stream);
 
 /* RMS normalisation over the last dimension with `n_gain` gain vectors: row r uses gain[r % n_gain]
  * (n_gain = 4 over rows [.,4,d] is the Grouped RMSNorm of the down-sampler).  x, y: dev elem [M][d];
@@ -284,22 +288,15 @@ size_t sf_argmax_workspace_bytes(int32_t M);
 sf_status sf_op_argmax(const sf_ctx *ctx, const float *logits, int32_t M, int32_t V, int32_t *ids,
                        void *workspace, size_t workspace_bytes, void *stream);
 
-/* Measurement aid.  Between sf_profile_begin and sf_profile_end every kernel launch of this context
- * is bracketed by a pair of HIP events on its stream.  sf_profile_end waits for the last one and
- * returns, per kernel class, the summed duration in ms and the number of launches (host arrays of
- * n_class >= SF_N_KERNEL_CLASSES entries).  Classes: 0 linear (GEMM), 1 attention, 2 attention
- * split-KV combine, 3 RMSNorm, 4 rotary + K/V append, 5 SwiGLU gate, 6 embedding / hook copies,
- * 7 arg-max pass over the logits, 8 arg-max finish / accept-commit. */
-#define SF_N_KERNEL_CLASSES 9
-/* Measurement aid: a plain device-to-device copy kernel (`calib_copy_kernel`) of `bytes` (multiple of 16,
- * 16-byte aligned pointers) that reads and writes every byte exactly once: the dispatch of known size
- * against which hardware byte counters (FETCH_SIZE, WRITE_SIZE) are scaled. */
-sf_status sf_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
-sf_status sf_profile_begin(sf_ctx *ctx);
-sf_status sf_profile_end(sf_ctx *ctx, double *ms, int32_t *launches, int32_t n_class);
+/* The acceptance rule alone, on explicit state arrays (what sf_accept_commit launches after its call-order
+ * check): all pointers dev; kv_len, pending: [B] in/out; n_new: [B] out; cu_new: [B+1] out. */
+sf_status sf_op_accept(const sf_ctx *ctx, int32_t B, int32_t k, const int32_t *draft_tokens,
+                       const int32_t *target_ids, const int32_t *force_len, int32_t *accept_len,
+                       int32_t *out_tokens, int32_t *kv_len, int32_t *pending, int32_t *n_new, int32_t *cu_new,
+                       void *stream);
 
 const char *sf_strerror(sf_status s);
-/* HIP error code of the last SF_EHIP on this context (0 if none). host. */
+/* HIP error code (hipError_t) of the last SF_EHIP on this context, 0 if none. host. */
 int sf_last_hip_error(const sf_ctx *ctx);
 /* Library version, and the code-object architecture it was built for ("gfx950"). host. */
 const char *sf_version(void);

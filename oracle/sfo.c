@@ -32,10 +32,10 @@ static void round_buf(double *x, long n, int on) {
 /* y = RMSNorm(x; g) . w^T for the norm + linear pairs of the decoder layers.  Exact mode: the two
  * definitions one after the other.  bf16 emulation: the path under test stores neither the normalised
  * rows nor the gains separately -- the gain vector is folded into the weight's columns once (rounded
- * to bf16), the matrix product runs on the raw rows as a bf16 pipeline sees them (each element rounded
- * to bf16: the residual stream itself is kept wider, see sfo.h), and the row factor
- * 1/sqrt(mean(x^2)+eps), taken from the unrounded row, commutes with the sum over the features and is
- * applied unrounded -- so the emulation rounds w*g and the product's copy of x, and nothing else. */
+ * to bf16), the matrix product runs on the raw rows as a bf16 pipeline sees them (its bf16 copy of
+ * the row: the residual stream itself is kept wider, see sfo.h), and the row factor
+ * 1/sqrt(mean(x^2)+eps), taken from that same bf16 copy, commutes with the sum over the features and
+ * is applied unrounded -- so the emulation rounds w*g and x, and nothing else. */
 void sfo_norm_linear(const double *x, const float *g, const float *w, int M, int K, int N, double eps, int on,
                      double *y) {
   if (!on) {
@@ -52,13 +52,13 @@ void sfo_norm_linear(const double *x, const float *g, const float *w, int M, int
   for (long i = 0; i < (long)M * K; ++i) xr[i] = sfo_round_bf16(x[i]);
   sfo_linear(xr, wf, NULL, M, K, N, y);
   free(wf);
-  free(xr);
   for (int r = 0; r < M; ++r) {
     double ss = 0.0;
-    for (int e = 0; e < K; ++e) ss += x[(long)r * K + e] * x[(long)r * K + e];
+    for (int e = 0; e < K; ++e) ss += xr[(long)r * K + e] * xr[(long)r * K + e];
     double rinv = 1.0 / sqrt(ss / K + eps);
     for (int n = 0; n < N; ++n) y[(long)r * N + n] *= rinv;
   }
+  free(xr);
 }
 
 void sfo_rmsnorm(const double *x, const float *g, int M, int d, double eps, double *y) {

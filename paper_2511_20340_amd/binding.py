@@ -1,4 +1,4 @@
-"""ctypes mirror of include/specformer.h.  Argument marshalling only."""
+"""ctypes mirror of include/specformer.h and include/specformer_aux.h.  Argument marshalling only."""
 import ctypes as C
 import os
 
@@ -15,8 +15,14 @@ KERNEL_CLASSES = ["linear", "attention", "attention_combine", "rmsnorm", "rope_k
 EXPORTS = [
     "sf_create", "sf_destroy", "sf_workspace_bytes", "sf_kv_cache_bytes", "sf_bind", "sf_draft_step",
     "sf_verify_step", "sf_accept_commit", "sf_kv_import", "sf_kv_export", "sf_attention_workspace_bytes",
-    "sf_op_attention", "sf_packed_weight_bytes", "sf_pack_weight", "sf_linear_workspace_bytes", "sf_op_linear", "sf_op_rmsnorm_linear", "sf_op_linear_swiglu", "sf_tune_linear", "sf_linear_num_tiles", "sf_linear_config", "sf_tune_attention", "sf_op_rmsnorm", "sf_op_rope_kv_append", "sf_rope_attention_workspace_bytes", "sf_op_rope_attention", "sf_op_silu_mul",
-    "sf_argmax_workspace_bytes", "sf_op_argmax", "sf_calib_copy", "sf_profile_begin", "sf_profile_end", "sf_strerror", "sf_last_hip_error", "sf_version",
+    "sf_op_attention", "sf_packed_weight_bytes", "sf_pack_weight", "sf_linear_workspace_bytes", "sf_op_linear",
+    "sf_op_rmsnorm_linear", "sf_op_linear_swiglu", "sf_linear_argmax_workspace_bytes", "sf_op_linear_argmax",
+    "sf_op_rmsnorm", "sf_op_rope_kv_append", "sf_rope_attention_workspace_bytes", "sf_op_rope_attention",
+    "sf_op_silu_mul", "sf_argmax_workspace_bytes", "sf_op_argmax", "sf_op_accept", "sf_strerror",
+    "sf_last_hip_error", "sf_version",
+    # include/specformer_aux.h
+    "sf_tune_linear", "sf_linear_num_tiles", "sf_linear_config", "sf_tune_attention", "sf_calib_copy",
+    "sf_profile_begin", "sf_profile_end",
 ]
 
 vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
@@ -75,8 +81,12 @@ def lib():
     L.sf_kv_cache_bytes.restype = sz
     L.sf_bind.argtypes = [vp, P(TargetWeights), P(DraftWeights)]
     L.sf_draft_step.argtypes = [vp, P(State), i32, i32, i32, vp, vp, vp]
-    L.sf_verify_step.argtypes = [vp, P(State), i32, vp, i32, vp, vp]
+    L.sf_verify_step.argtypes = [vp, P(State), i32, vp, i32, vp, vp, vp]
     L.sf_accept_commit.argtypes = [vp, P(State), i32, vp, vp, vp, vp, vp, vp]
+    L.sf_op_accept.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.sf_linear_argmax_workspace_bytes.argtypes = [vp, i32, i32]
+    L.sf_linear_argmax_workspace_bytes.restype = sz
+    L.sf_op_linear_argmax.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     L.sf_kv_import.argtypes = [vp, vp, vp, i32, i32, i32, vp]
     L.sf_kv_export.argtypes = [vp, vp, vp, i32, i32, i32, vp]
     L.sf_attention_workspace_bytes.argtypes = [vp, i32, i32, i32]
@@ -90,11 +100,11 @@ def lib():
     L.sf_op_linear_swiglu.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, sz, vp]
     L.sf_linear_workspace_bytes.argtypes = [vp, i32]
     L.sf_linear_workspace_bytes.restype = sz
-    L.sf_tune_linear.argtypes = [i32, i32]
+    L.sf_tune_linear.argtypes = [vp, i32, i32]
     L.sf_linear_num_tiles.argtypes = []
     L.sf_linear_num_tiles.restype = i32
     L.sf_linear_config.argtypes = [i32, i32, i32, i32, C.c_size_t, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
-    L.sf_tune_attention.argtypes = [i32]
+    L.sf_tune_attention.argtypes = [vp, i32]
     L.sf_op_rmsnorm.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
     L.sf_op_rope_kv_append.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
     L.sf_rope_attention_workspace_bytes.argtypes = [vp, i32, i32, i32]

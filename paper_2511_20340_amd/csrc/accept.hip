@@ -2,8 +2,10 @@
 // streaming read of the fp32 logits), draft/target comparison, longest accepted prefix, commit of
 // lengths / pending tokens, exclusive scan of the accept lengths.
 //
-// Pass 1 splits every logits row into ARGMAX_SEGS segments so that B*(k+1) rows give thousands of
-// workgroups; pass 2 is one workgroup that finishes the arg-max, compares, commits and scans.
+// The arg-max normally arrives as per-column-tile partials from the LM-head kernel's epilogue (the
+// logits are then never stored); argmax_partial_kernel produces the same kind of partials from
+// materialised logits (16 segments per row, thousands of workgroups).  argmax_final_kernel finishes
+// a row's partials; accept_kernel is one workgroup that compares, commits and scans.
 // Ties resolve to the lowest index; NaN never wins; a row without any comparable value gives 0.
 #include "sf_internal.h"
 #include <limits.h>
@@ -55,20 +57,28 @@ __global__ __launch_bounds__(256) void argmax_partial_kernel(const float *__rest
   }
 }
 
-__device__ __forceinline__ int32_t row_argmax(const float *pmax, const int32_t *pidx, int row) {
+// One wavefront per row: the best of the row's n_part partials (ascending column ranges, so the
+// lowest index wins among equal values).
+__global__ __launch_bounds__(256) void argmax_final_kernel(const float *__restrict__ pmax,
+                                                           const int32_t *__restrict__ pidx, int M, int n_part,
+                                                           int stride, int32_t *__restrict__ ids) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= M) return;
   Best b{-__builtin_huge_valf(), INT_MAX};
-  for (int s = 0; s < ARGMAX_SEGS; ++s) b = better(b, Best{pmax[row * ARGMAX_SEGS + s], pidx[row * ARGMAX_SEGS + s]});
-  return b.i == INT_MAX ? 0 : b.i;
+  for (int s = lane; s < n_part; s += 64) {
+    const int32_t i = pidx[(size_t)row * stride + s];
+    if (i != INT_MAX) b = better(b, Best{pmax[(size_t)row * stride + s], i});
+  }
+  for (int o = 32; o; o >>= 1) {
+    Best other{__shfl_xor(b.v, o), __shfl_xor(b.i, o)};
+    b = better(b, other);
+  }
+  if (lane == 0) ids[row] = b.i == INT_MAX ? 0 : b.i;
 }
 
-__global__ void argmax_final_kernel(const float *__restrict__ pmax, const int32_t *__restrict__ pidx, int M,
-                                    int32_t *__restrict__ ids) {
-  const int row = blockIdx.x * blockDim.x + threadIdx.x;
-  if (row < M) ids[row] = row_argmax(pmax, pidx, row);
-}
-
-// One workgroup.  Thread t owns the sequences [t*per, (t+1)*per).
-__global__ __launch_bounds__(256) void accept_kernel(const float *__restrict__ pmax, const int32_t *__restrict__ pidx,
+// One workgroup.  Thread t owns the sequences [t*per, (t+1)*per): their accept lengths from the
+// target's choices p and the draft, the commit, and a workgroup-wide scan for the offsets.
+__global__ __launch_bounds__(256) void accept_kernel(const int32_t *__restrict__ target_ids,
                                                      const int32_t *__restrict__ draft,
                                                      const int32_t *__restrict__ force_len,
                                                      int32_t *__restrict__ accept_len, int32_t *__restrict__ out_tokens,
@@ -81,15 +91,13 @@ __global__ __launch_bounds__(256) void accept_kernel(const float *__restrict__ p
   const int b0 = threadIdx.x * per, b1 = min(B, b0 + per);
   int32_t local = 0;
   for (int b = b0; b < b1; ++b) {
-    int32_t p[16];
-    for (int i = 0; i < q; ++i) p[i] = row_argmax(pmax, pidx, b * q + i);
+    const int32_t *p = target_ids + (size_t)b * q;
     int a;
     if (force_len) {
       a = min(max(force_len[b], 0), q);
     } else {
-      int n = 0;
-      while (n < k && draft[b * k + n] == p[n]) ++n;
-      a = n + 1;
+      a = 1;
+      for (int n = 0; n < k && draft[b * k + n] == p[n]; ++n) a = n + 2;
     }
     for (int i = 0; i < q; ++i) out_tokens[b * q + i] = i < a ? p[i] : -1;
     accept_len[b] = a;
@@ -112,7 +120,6 @@ __global__ __launch_bounds__(256) void accept_kernel(const float *__restrict__ p
     run += n_new[b];
   }
   if (b1 == B && b0 < B) cu_new[B] = run;
-  if (B == 0 && threadIdx.x == 0) cu_new[0] = 0;
 }
 
 }  // namespace
@@ -122,13 +129,14 @@ hipError_t launch_argmax_partial(const float *logits, int M, int V, float *pmax,
   return hipGetLastError();
 }
 
-hipError_t launch_argmax_final(const float *pmax, const int32_t *pidx, int M, int32_t *ids, hipStream_t s) {
-  argmax_final_kernel<<<(M + 255) / 256, 256, 0, s>>>(pmax, pidx, M, ids);
+hipError_t launch_argmax_final(const float *pmax, const int32_t *pidx, int M, int n_part, int stride, int32_t *ids,
+                               hipStream_t s) {
+  argmax_final_kernel<<<(M + 3) / 4, 256, 0, s>>>(pmax, pidx, M, n_part, stride, ids);
   return hipGetLastError();
 }
 
 hipError_t launch_accept(const AcceptArgs &a, hipStream_t s) {
-  accept_kernel<<<1, 256, 0, s>>>(a.pmax, a.pidx, a.draft, a.force_len, a.accept_len, a.out_tokens, a.kv_len,
+  accept_kernel<<<1, 256, 0, s>>>(a.target_ids, a.draft, a.force_len, a.accept_len, a.out_tokens, a.kv_len,
                                   a.pending, a.n_new, a.cu_new, a.B, a.k);
   return hipGetLastError();
 }

@@ -5,6 +5,7 @@
 #include <new>
 #include <vector>
 #include "sf_internal.h"
+#include "../../include/specformer_aux.h"
 
 #include <cstddef>
 
@@ -29,6 +30,12 @@ struct sf_ctx {
   sf_draft_weights dw;
   std::vector<const void *> attn_norm, wqkv, wo, ffn_norm, w_gate_up, w_down;
   mutable int hip_err;
+  // call order: the block that sf_verify_step wrote behind the prefixes and that no sf_accept_commit has
+  // committed yet (state identified by its kv_len buffer); k < 0: none
+  const void *verified_state = nullptr;
+  int verified_k = -1;
+  // tuning overrides of this context (0 = automatic)
+  int tune_tile = 0, tune_split = 0, tune_chunk = 0;
 };
 
 namespace {
@@ -41,8 +48,8 @@ size_t esize(int dtype) { return dtype == SF_BF16 ? 2 : 4; }
 // (B*(max_k+1) rows) and draft-slot (B*k rows) uses; draft and verify run back to back on one
 // stream, so they share it.
 struct Arena {
-  size_t h, a, qkv, qr, ao, gu, act, table, order, part_o, part_ml, pmax, pidx;  // shared
-  size_t f4, x, kvc, xl, s0, dlogits;                                    // draft only
+  size_t h, hb, a, qkv, qr, ao, gu, act, table, order, part_o, part_ml, pmax, pidx, logits;  // shared
+  size_t f4, x, kvc, xl, s0, s0b;                                        // draft only
   size_t x_last, id_last, q1, qr1, ao1, len_m1, zeros, kc2, vc2;         // draft, two-stage wiring
   size_t gemm_ws, gemm_ws_bytes;
   size_t total;
@@ -64,7 +71,8 @@ Arena plan(const sf_ctx *c, int B, int k, int cap) {
   a.gemm_ws_bytes = m.dtype == SF_BF16 ? gemm_workspace_bytes((int)Mx) : 0;
   a.gemm_ws = take(a.gemm_ws_bytes);
   a.zeros = take((size_t)B * sizeof(int32_t));  // likewise never written: the empty prefix of a slot-only attention
-  a.h = take(M * d * es);
+  a.h = take(M * d * sizeof(float));  // the residual stream
+  a.hb = take(m.dtype == SF_BF16 ? M * d * es : 0);
   a.a = take(Mx * d * es);
   a.qkv = take(M * (nq + 2 * nkv) * es);
   a.qr = take(M * nq * es);
@@ -78,16 +86,19 @@ Arena plan(const sf_ctx *c, int B, int k, int cap) {
   const size_t rows_part = part / ((m.head_dim + 2) * sizeof(float));
   a.part_o = take(rows_part * m.head_dim * sizeof(float));
   a.part_ml = take(rows_part * 2 * sizeof(float));
-  a.pmax = take(Mx * ARGMAX_SEGS * sizeof(float));
-  a.pidx = take(Mx * ARGMAX_SEGS * sizeof(int32_t));
+  // arg-max partials: per row one entry per column tile of the LM head (bf16) or per segment (fp32)
+  const size_t parts = m.dtype == SF_BF16 ? (size_t)gemm_argmax_parts((int)V) : (size_t)ARGMAX_SEGS;
+  a.pmax = take(Mx * parts * sizeof(float));
+  a.pidx = take(Mx * parts * sizeof(int32_t));
+  a.logits = take(m.dtype == SF_F32 ? Mx * V * sizeof(float) : 0);  // fp32 mode materialises them
   a.f4 = take(Mh * 4 * d * es);
   a.x = take(Mh * d * es);
   a.kvc = take(Mh * 2 * nkv * es);
   a.xl = take((size_t)B * d * es);
-  a.s0 = take(Ms * d * es);
-  a.dlogits = take(Ms * V * sizeof(float));
+  a.s0 = take(Ms * d * sizeof(float));  // the slot layer's residual stream
+  a.s0b = take(m.dtype == SF_BF16 ? Ms * d * es : 0);
   a.x_last = take((size_t)B * d * es);
-  a.id_last = take((size_t)B * d * es);
+  a.id_last = take((size_t)B * d * sizeof(float));
   a.q1 = take((size_t)B * nq * es);
   a.qr1 = take((size_t)B * nq * es);
   a.ao1 = take((size_t)B * nq * es);
@@ -147,13 +158,50 @@ struct Run {
 };
 #define LAUNCH(cls, expr) r.launch(cls, [&] { return (expr); })
 
+// optional extras of one linear launch (bf16 mode)
+struct GemmExtra {
+  int res_f32 = 0;               // residual (and, with out_f32, y) are rows of the float residual stream
+  void *y2 = nullptr;            // bf16 copy of y
+  void *hooks = nullptr;         // hooked copies of the block rows
+  int hook_mask = 0, hook_q = 1, hook_qmax = 1;
+  float *am_val = nullptr;       // arg-max partials per column tile
+  int32_t *am_idx = nullptr;
+  int am_stride = 0;
+  int *am_parts_out = nullptr;
+};
+
 void gemm(Run &r, int dtype, const void *x, const void *w, const void *bias, const void *res, void *y, int M, int N,
-          int K, int out_f32, int glu = 0, int fused_norm = 0, float norm_eps = 0.f) {
+          int K, int out_f32, int glu = 0, int fused_norm = 0, float norm_eps = 0.f, const GemmExtra *ex = nullptr) {
   if (r.st != SF_OK) return;
   GemmArgs g{x, w, bias, res, y, M, N, K, out_f32, glu, r.gemm_ws, r.gemm_ws_bytes};
   g.plan_M = r.plan_rows;
+  g.tile = r.c->tune_tile; g.split = r.c->tune_split;
   g.fused_norm = fused_norm; g.norm_eps = norm_eps;
+  if (ex && dtype == SF_BF16) {
+    g.res_f32 = ex->res_f32; g.y2 = ex->y2; g.hooks = ex->hooks; g.hook_mask = ex->hook_mask; g.hook_q = ex->hook_q;
+    g.hook_qmax = ex->hook_qmax; g.am_val = ex->am_val; g.am_idx = ex->am_idx; g.am_stride = ex->am_stride;
+    g.am_parts_out = ex->am_parts_out;
+  }
   LAUNCH(K_GEMM, dtype == SF_BF16 ? launch_gemm_bf16(g, r.s) : launch_gemm_f32(g, r.s));
+}
+
+// LM head + arg-max: ids[row] = argmax_v (a . lm_head^T)[row][v].  bf16: the linear kernel's epilogue leaves
+// per-column-tile partials and the logits are stored only when `logits` is given; fp32: the logits are
+// materialised (in `logits`, else in `scratch_logits`) and scanned in segments.
+void lm_head_argmax(Run &r, const sf_model_cfg &m, const void *a, const void *lm_head, float *logits,
+                    float *scratch_logits, float *pmax, int32_t *pidx, int32_t *ids, int M) {
+  if (m.dtype == SF_BF16) {
+    GemmExtra ex;
+    int parts = 0;  // column tiles of the launch's tile shape: the partials it writes per row
+    ex.am_val = pmax; ex.am_idx = pidx; ex.am_stride = gemm_argmax_parts(m.vocab); ex.am_parts_out = &parts;
+    gemm(r, m.dtype, a, lm_head, nullptr, nullptr, logits, M, m.vocab, m.d_model, 1, 0, 0, 0.f, &ex);
+    LAUNCH(K_ACCEPT, launch_argmax_final(pmax, pidx, M, parts, ex.am_stride, ids, r.s));
+  } else {
+    float *lg = logits ? logits : scratch_logits;
+    gemm(r, m.dtype, a, lm_head, nullptr, nullptr, lg, M, m.vocab, m.d_model, 1);
+    LAUNCH(K_ARGMAX, launch_argmax_partial(lg, M, m.vocab, pmax, pidx, r.s));
+    LAUNCH(K_ACCEPT, launch_argmax_final(pmax, pidx, M, ARGMAX_SEGS, ARGMAX_SEGS, ids, r.s));
+  }
 }
 
 // act[M][F] = silu(a . Wg^T) * (a . Wu^T): one kernel in bf16 mode (weight packed with glu = 1), GEMM to
@@ -169,29 +217,31 @@ void swiglu_in(Run &r, int dtype, const void *a, const void *w_gate_up, float *g
 }
 
 void norm(Run &r, const sf_model_cfg &m, const void *x, const void *gain, void *y, int M, int n_gain = 1,
-          int map = 0, int q = 1, int q_max = 1, const int32_t *n_new = nullptr) {
+          int map = 0, int q = 1, int q_max = 1, const int32_t *n_new = nullptr, int x_f32 = 0) {
   if (r.st != SF_OK) return;
-  NormArgs n{x, gain, y, M, m.d_model, n_gain, m.rms_eps, map, q, q_max, n_new};
+  NormArgs n{x, gain, y, M, m.d_model, n_gain, m.rms_eps, map, q, q_max, n_new, x_f32};
   LAUNCH(K_NORM, launch_rmsnorm(n, m.dtype, r.s));
 }
 
 // y = RMSNorm(x; gain) . w^T.  bf16: ONE kernel -- w was packed with the gain folded into its columns,
 // the linear kernel takes the raw rows, sums their squares while staging them and scales its
 // accumulators by the row factor.  fp32: the norm kernel into `tmp`, then the linear kernel.
-void norm_gemm(Run &r, const sf_model_cfg &m, const void *x, const void *gain, void *tmp, const void *w, void *y,
-               int M, int N, int K, int out_f32) {
+// x: the rows in fp32 mode; xb: their bf16 copy in bf16 mode (rows of the residual stream are kept as float
+// plus a bf16 copy for exactly this use).
+void norm_gemm(Run &r, const sf_model_cfg &m, const void *x, const void *xb, const void *gain, void *tmp,
+               const void *w, void *y, int M, int N, int K, int out_f32) {
   if (m.dtype == SF_BF16) {
-    gemm(r, m.dtype, x, w, nullptr, nullptr, y, M, N, K, out_f32, 0, 1, m.rms_eps);
+    gemm(r, m.dtype, xb, w, nullptr, nullptr, y, M, N, K, out_f32, 0, 1, m.rms_eps);
   } else {
     norm(r, m, x, gain, tmp, M);
     gemm(r, m.dtype, tmp, w, nullptr, nullptr, y, M, N, K, out_f32);
   }
 }
 
-void norm_swiglu_in(Run &r, const sf_model_cfg &m, const void *x, const void *gain, void *tmp, const void *w_gate_up,
-                    float *gu, void *act, int M, int F, int K) {
+void norm_swiglu_in(Run &r, const sf_model_cfg &m, const void *x, const void *xb, const void *gain, void *tmp,
+                    const void *w_gate_up, float *gu, void *act, int M, int F, int K) {
   if (m.dtype == SF_BF16) {
-    swiglu_in(r, m.dtype, x, w_gate_up, gu, act, M, F, K, 1, m.rms_eps);
+    swiglu_in(r, m.dtype, xb, w_gate_up, gu, act, M, F, K, 1, m.rms_eps);
   } else {
     norm(r, m, x, gain, tmp, M);
     swiglu_in(r, m.dtype, tmp, w_gate_up, gu, act, M, F, K);
@@ -206,7 +256,7 @@ void attention(Run &r, const sf_model_cfg &m, const void *q, const void *kc, con
   a.q = q; a.qkv = qkv; a.table = table; a.order = order; a.kc = kc; a.vc = vc; a.kv_len = kv_len; a.out = out; a.part_o = part_o; a.part_ml = part_ml;
   a.B = B; a.n_q = n_q; a.Hq = m.n_q_heads; a.Hkv = m.n_kv_heads; a.hd = m.head_dim; a.cap = cap; a.mode = mode;
   const int n_rt = (m.n_q_heads / m.n_kv_heads * n_q + 31) / 32;
-  a.chunk_tiles = attn_chunk_tiles(B * m.n_kv_heads * n_rt, len_upper + n_q);
+  a.chunk_tiles = r.c->tune_chunk > 0 ? r.c->tune_chunk : attn_chunk_tiles(B * m.n_kv_heads * n_rt, len_upper + n_q);
   const int n_tiles = (len_upper + n_q + TK - 1) / TK;
   a.n_chunks = (n_tiles + a.chunk_tiles - 1) / a.chunk_tiles;
   LAUNCH(K_ATTN, m.dtype == SF_BF16 ? launch_attention_bf16(a, r.s) : launch_attention_f32(a, r.s));
@@ -305,26 +355,37 @@ sf_status sf_bind(sf_ctx *c, const sf_target_weights *t, const sf_draft_weights 
 }
 
 sf_status sf_verify_step(sf_ctx *c, const sf_state *st, int32_t k, const int32_t *draft, int32_t len_upper,
-                         float *logits, void *stream) {
+                         float *logits, int32_t *target_ids, void *stream) {
   sf_status v = check_state(c, st, k, false);
   if (v != SF_OK) return v;
-  if (!logits || (k > 0 && !draft) || len_upper < 0) return SF_EINVAL;
+  if (!target_ids || (k > 0 && !draft) || len_upper < 0) return SF_EINVAL;
   const sf_model_cfg &m = c->tc;
   const int B = st->B, q = k + 1, M = B * q, cap = st->cap, qm = c->max_k + 1;
   if ((long)len_upper + q > cap) return SF_ECAPACITY;
   if ((v = check_attn_shape(m, q)) != SF_OK) return v;
   const Arena A = plan(c, B, k, cap);
   char *ws = (char *)st->workspace;
-  void *h = ws + A.h, *a = ws + A.a, *qkv = ws + A.qkv, *qr = ws + A.qr, *ao = ws + A.ao, *act = ws + A.act;
+  float *h = (float *)(ws + A.h);                                    // the residual stream
+  void *hb = m.dtype == SF_BF16 ? (void *)(ws + A.hb) : (void *)h;   // bf16: its copy for the matrix products
+  void *a = ws + A.a, *qkv = ws + A.qkv, *qr = ws + A.qr, *ao = ws + A.ao, *act = ws + A.act;
   float *gu = (float *)(ws + A.gu);
   const int d = m.d_model, F = m.d_ffn, L = m.n_layers;
   const int nq = m.n_q_heads * m.head_dim, nkv = m.n_kv_heads * m.head_dim;
+  const bool bf = m.dtype == SF_BF16;
   Run r{c, (hipStream_t)stream};
   r.gemm_ws = ws + A.gemm_ws; r.gemm_ws_bytes = A.gemm_ws_bytes;
   // the target's logits for a position must not depend on how many draft positions are verified
   // with it: every k of this state uses the K partition chosen for the largest block
   r.plan_rows = B * qm;
-  LAUNCH(K_EMBED_HOOK, launch_embed(c->tw.embed, st->pending, draft, h, st->hooks, B, k, qm, d, m.vocab, m.dtype, r.s));
+  // hooked states: group g holds the stream after layer hook_layer[g] (0 = the embedding)
+  const int hook_layer[4] = {0, L / 2, L - 1, L};
+  auto hook_mask_of = [&](int l) {
+    int mask = 0;
+    for (int g = 0; g < 4; ++g) mask |= (hook_layer[g] == l) << g;
+    return mask;
+  };
+  LAUNCH(K_EMBED_HOOK, launch_embed(c->tw.embed, st->pending, draft, h, bf ? hb : nullptr, st->hooks, hook_mask_of(0),
+                                    B, k, qm, d, m.vocab, m.dtype, r.s));
   RopeArgs ra{};
   ra.qkv = qkv; ra.q_out = qr; ra.kv_len = st->kv_len; ra.n_new = nullptr; ra.table = (float2 *)(ws + A.table);
   ra.B = B; ra.n_q = q; ra.Hq = m.n_q_heads; ra.Hkv = m.n_kv_heads; ra.hd = m.head_dim; ra.cap = cap;
@@ -332,29 +393,34 @@ sf_status sf_verify_step(sf_ctx *c, const sf_state *st, int32_t k, const int32_t
   // bf16, more attention workgroups than the chip holds at once (2 per CU): the table kernel also ranks
   // the sequences by length, and the attention launches of this call start the longest first
   const int attn_groups = B * m.n_kv_heads * ((m.n_q_heads / m.n_kv_heads * q + 31) / 32);
-  ra.order = m.dtype == SF_BF16 && attn_groups > 512 ? (int32_t *)(ws + A.order) : nullptr;
+  ra.order = bf && attn_groups > 512 ? (int32_t *)(ws + A.order) : nullptr;
   LAUNCH(K_ROPE, launch_rope_table(ra, r.s));
-  const int hook_layer[4] = {0, L / 2, L - 1, L};
   const size_t lb = kv_layer_bytes(m, B, cap);
-  for (int l = 0; l <= L && r.st == SF_OK; ++l) {
-    for (int g = 1; g < 4; ++g)
-      if (hook_layer[g] == l) LAUNCH(K_EMBED_HOOK, launch_hook_copy(h, st->hooks, B, q, qm, d, g, m.dtype, r.s));
-    if (l == L) break;
+  for (int l = 0; l < L && r.st == SF_OK; ++l) {
     void *kc = (char *)st->tk + l * lb, *vc = (char *)st->tv + l * lb;
-    norm_gemm(r, m, h, c->attn_norm[l], a, c->wqkv[l], qkv, M, nq + 2 * nkv, d, 0);
+    norm_gemm(r, m, h, hb, c->attn_norm[l], a, c->wqkv[l], qkv, M, nq + 2 * nkv, d, 0);
     ra.kc = kc; ra.vc = vc;
     // bf16: the attention kernel rotates Q and K and appends the block's K, V rows itself
-    const bool fused_rope = m.dtype == SF_BF16;
-    if (!fused_rope) LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
+    if (!bf) LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
     attention(r, m, qr, kc, vc, st->kv_len, ao, (float *)(ws + A.part_o), (float *)(ws + A.part_ml), B, q, cap,
-              SF_MASK_CAUSAL, len_upper, fused_rope ? qkv : nullptr, ra.table, ra.order);
-    gemm(r, m.dtype, ao, c->wo[l], nullptr, h, h, M, d, nq, 0);
-    norm_swiglu_in(r, m, h, c->ffn_norm[l], a, c->w_gate_up[l], gu, act, M, F, d);
-    gemm(r, m.dtype, act, c->w_down[l], nullptr, h, h, M, d, F, 0);
+              SF_MASK_CAUSAL, len_upper, bf ? qkv : nullptr, ra.table, ra.order);
+    // h += attention . W_O, and h += W_down . act: float sums; bf16 mode also refreshes the bf16 copy
+    GemmExtra ex;
+    ex.res_f32 = 1; ex.y2 = hb;
+    gemm(r, m.dtype, ao, c->wo[l], nullptr, h, h, M, d, nq, 1, 0, 0, 0.f, &ex);
+    norm_swiglu_in(r, m, h, hb, c->ffn_norm[l], a, c->w_gate_up[l], gu, act, M, F, d);
+    const int mask = hook_mask_of(l + 1);  // the stream after this layer is hooked state(s) `mask`
+    if (mask) { ex.hooks = st->hooks; ex.hook_mask = mask; ex.hook_q = q; ex.hook_qmax = qm; }
+    gemm(r, m.dtype, act, c->w_down[l], nullptr, h, h, M, d, F, 1, 0, 0, 0.f, &ex);
+    if (!bf)
+      for (int g = 1; g < 4; ++g)
+        if (mask >> g & 1) LAUNCH(K_EMBED_HOOK, launch_hook_copy(h, st->hooks, B, q, qm, d, g, m.dtype, r.s));
   }
   // the LM head serves two norms (this one and the draft's), so no gain is folded into it
-  norm(r, m, h, c->tw.final_norm, a, M);
-  gemm(r, m.dtype, a, c->tw.lm_head, nullptr, nullptr, logits, M, m.vocab, d, 1);
+  norm(r, m, h, c->tw.final_norm, a, M, 1, 0, 1, 1, nullptr, 1);
+  lm_head_argmax(r, m, a, c->tw.lm_head, logits, (float *)(ws + A.logits), (float *)(ws + A.pmax),
+                 (int32_t *)(ws + A.pidx), target_ids, M);
+  if (r.st == SF_OK) { c->verified_state = st->kv_len; c->verified_k = k; }
   return r.st;
 }
 
@@ -375,9 +441,12 @@ sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, 
   if (two_stage && k > TK) return SF_EUNSUPPORTED;
   const Arena A = plan(c, B, k, cap);
   char *ws = (char *)st->workspace;
+  const bool bf = m.dtype == SF_BF16;
   void *a = ws + A.a, *qkv = ws + A.qkv, *qr = ws + A.qr, *ao = ws + A.ao, *act = ws + A.act;
-  void *f4 = ws + A.f4, *x = ws + A.x, *kvc = ws + A.kvc, *xl = ws + A.xl, *s0 = ws + A.s0;
-  float *gu = (float *)(ws + A.gu), *dlogits = draft_logits ? draft_logits : (float *)(ws + A.dlogits);
+  void *f4 = ws + A.f4, *x = ws + A.x, *kvc = ws + A.kvc, *xl = ws + A.xl;
+  float *s0 = (float *)(ws + A.s0);                                    // the slot layer's residual stream
+  void *s0b = bf ? (void *)(ws + A.s0b) : (void *)s0;                  // bf16: its copy for the matrix products
+  float *gu = (float *)(ws + A.gu);
   float *part_o = (float *)(ws + A.part_o), *part_ml = (float *)(ws + A.part_ml);
   const int d = m.d_model, F = m.d_ffn;
   const int nq = m.n_q_heads * m.head_dim, nkv = m.n_kv_heads * m.head_dim;
@@ -388,8 +457,8 @@ sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, 
   norm(r, m, st->hooks, w.group_norm, f4, Mh * 4, 4, 1, qm, qm, nullptr);
   gemm(r, m.dtype, f4, w.w_ds, nullptr, nullptr, x, Mh, d, 4 * d, 0);
   // K and V rows of wqkv start after the nq query rows (a whole number of packed 32-row blocks)
-  const size_t kv_off = m.dtype == SF_BF16 ? packed_weight_bytes(nq, d, m.dtype) : (size_t)nq * d * es;
-  norm_gemm(r, m, x, w.attn_norm, a, (const char *)w.wqkv + kv_off, kvc, Mh, 2 * nkv, d, 0);
+  const size_t kv_off = bf ? packed_weight_bytes(nq, d, m.dtype) : (size_t)nq * d * es;
+  norm_gemm(r, m, x, x, w.attn_norm, a, (const char *)w.wqkv + kv_off, kvc, Mh, 2 * nkv, d, 0);
   RopeArgs ra{};
   ra.qkv = kvc; ra.q_out = nullptr; ra.kc = st->dk; ra.vc = st->dv; ra.kv_len = st->kv_len; ra.n_new = st->n_new;
   ra.table = (float2 *)(ws + A.table);
@@ -407,10 +476,11 @@ sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, 
   } else {
     // The context attention's own output at the newest row (its K/V are in the cache by now):
     // I_D = X + W_O . attention(RoPE(W_Q . RMS(X)), keys up to and including the row itself).
-    void *x_last = ws + A.x_last, *id_last = ws + A.id_last, *q1 = ws + A.q1, *qr1 = ws + A.qr1, *ao1 = ws + A.ao1;
+    void *x_last = ws + A.x_last, *q1 = ws + A.q1, *qr1 = ws + A.qr1, *ao1 = ws + A.ao1;
+    float *id_last = (float *)(ws + A.id_last);
     int32_t *len_m1 = (int32_t *)(ws + A.len_m1);
     LAUNCH(K_EMBED_HOOK, launch_gather_last(x, x_last, st->n_new, st->kv_len, len_m1, B, qm, d, m.dtype, r.s));
-    norm_gemm(r, m, x_last, w.attn_norm, a, w.wqkv, q1, B, nq, d, 0);  // the nq query rows lead wqkv
+    norm_gemm(r, m, x_last, x_last, w.attn_norm, a, w.wqkv, q1, B, nq, d, 0);  // the nq query rows lead wqkv
     RopeArgs rq{};
     rq.qkv = q1; rq.q_out = qr1; rq.kc = nullptr; rq.vc = nullptr; rq.kv_len = len_m1; rq.n_new = nullptr;
     rq.table = ra.table; rq.B = B; rq.n_q = 1; rq.Hq = m.n_q_heads; rq.Hkv = 0; rq.hd = m.head_dim; rq.cap = cap;
@@ -418,43 +488,57 @@ sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, 
     LAUNCH(K_ROPE, launch_rope_table(rq, r.s));
     LAUNCH(K_ROPE, launch_rope_kv(rq, m.dtype, r.s));
     attention(r, m, qr1, st->dk, st->dv, len_m1, ao1, part_o, part_ml, B, 1, cap, SF_MASK_CAUSAL, len_upper);
-    gemm(r, m.dtype, ao1, w.wo, nullptr, x_last, id_last, B, d, nq, 0);
-    norm(r, m, id_last, w.pos_norm, xl, B, 1, 3, 1, 1, st->n_new);
+    gemm(r, m.dtype, ao1, w.wo, nullptr, x_last, id_last, B, d, nq, 1);  // float row of the stream
+    norm(r, m, id_last, w.pos_norm, xl, B, 1, 3, 1, 1, st->n_new, 1);
     // the slots attend to each other only: an empty prefix in a one-tile cache of their own
     norm_s = w.sa_norm; wqkv_s = w.sa_wqkv; wo_s = w.sa_wo;
     kc_s = ws + A.kc2; vc_s = ws + A.vc2; len_s = (const int32_t *)(ws + A.zeros);
     cap_s = TK; len_upper_s = 0;
   }
-  gemm(r, m.dtype, xl, w.w_pos, w.b_pos, nullptr, s0, B, k * d, d, 0);
+  GemmExtra ex;
+  ex.y2 = s0b;
+  gemm(r, m.dtype, xl, w.w_pos, w.b_pos, nullptr, s0, B, k * d, d, 1, 0, 0, 0.f, &ex);
   // one attention + SwiGLU layer over the slots
-  norm_gemm(r, m, s0, norm_s, a, wqkv_s, qkv, Ms, nq + 2 * nkv, d, 0);
+  norm_gemm(r, m, s0, s0b, norm_s, a, wqkv_s, qkv, Ms, nq + 2 * nkv, d, 0);
   ra.qkv = qkv; ra.q_out = qr; ra.kc = (void *)kc_s; ra.vc = (void *)vc_s; ra.kv_len = len_s; ra.n_new = nullptr;
   ra.n_q = k; ra.cap = cap_s; ra.kv_only = 0; ra.pos_mode = 0;
   LAUNCH(K_ROPE, launch_rope_table(ra, r.s));
   LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
   attention(r, m, qr, kc_s, vc_s, len_s, ao, part_o, part_ml, B, k, cap_s, mask, len_upper_s);
-  gemm(r, m.dtype, ao, wo_s, nullptr, s0, s0, Ms, d, nq, 0);
-  norm_swiglu_in(r, m, s0, w.ffn_norm, a, w.w_gate_up, gu, act, Ms, F, d);
-  gemm(r, m.dtype, act, w.w_down, nullptr, s0, s0, Ms, d, F, 0);
-  norm(r, m, s0, w.out_norm, a, Ms);
-  gemm(r, m.dtype, a, c->tw.lm_head, nullptr, nullptr, dlogits, Ms, m.vocab, d, 1);
-  LAUNCH(K_ARGMAX, launch_argmax_partial(dlogits, Ms, m.vocab, (float *)(ws + A.pmax), (int32_t *)(ws + A.pidx), r.s));
-  LAUNCH(K_ACCEPT, launch_argmax_final((float *)(ws + A.pmax), (int32_t *)(ws + A.pidx), Ms, draft_tokens, r.s));
+  ex.res_f32 = 1;
+  gemm(r, m.dtype, ao, wo_s, nullptr, s0, s0, Ms, d, nq, 1, 0, 0, 0.f, &ex);
+  norm_swiglu_in(r, m, s0, s0b, w.ffn_norm, a, w.w_gate_up, gu, act, Ms, F, d);
+  ex.y2 = nullptr;
+  gemm(r, m.dtype, act, w.w_down, nullptr, s0, s0, Ms, d, F, 1, 0, 0, 0.f, &ex);
+  norm(r, m, s0, w.out_norm, a, Ms, 1, 0, 1, 1, nullptr, 1);
+  lm_head_argmax(r, m, a, c->tw.lm_head, draft_logits, (float *)(ws + A.logits), (float *)(ws + A.pmax),
+                 (int32_t *)(ws + A.pidx), draft_tokens, Ms);
   return r.st;
 }
 
-sf_status sf_accept_commit(sf_ctx *c, const sf_state *st, int32_t k, const int32_t *draft, const float *logits,
+sf_status sf_accept_commit(sf_ctx *c, const sf_state *st, int32_t k, const int32_t *draft, const int32_t *target_ids,
                            const int32_t *force_len, int32_t *accept_len, int32_t *out_tokens, void *stream) {
   sf_status v = check_state(c, st, k, false);
   if (v != SF_OK) return v;
-  if (!logits || !accept_len || !out_tokens || (k > 0 && !draft && !force_len)) return SF_EINVAL;
-  const Arena A = plan(c, st->B, k, st->cap);
-  char *ws = (char *)st->workspace;
+  if (!target_ids || !accept_len || !out_tokens || (k > 0 && !draft && !force_len)) return SF_EINVAL;
+  // nothing to commit unless sf_verify_step wrote this very block (same state, same k) since the last commit
+  if (c->verified_state != st->kv_len || c->verified_k != k) return SF_ESTATE;
   Run r{c, (hipStream_t)stream};
-  const int M = st->B * (k + 1);
-  LAUNCH(K_ARGMAX, launch_argmax_partial(logits, M, c->tc.vocab, (float *)(ws + A.pmax), (int32_t *)(ws + A.pidx), r.s));
-  AcceptArgs a{(float *)(ws + A.pmax), (int32_t *)(ws + A.pidx), draft, force_len, accept_len, out_tokens,
-               st->kv_len, st->pending, st->n_new, st->cu_new, st->B, k};
+  AcceptArgs a{target_ids, draft, force_len, accept_len, out_tokens, st->kv_len, st->pending, st->n_new, st->cu_new,
+               st->B, k};
+  LAUNCH(K_ACCEPT, launch_accept(a, r.s));
+  if (r.st == SF_OK) { c->verified_state = nullptr; c->verified_k = -1; }
+  return r.st;
+}
+
+sf_status sf_op_accept(const sf_ctx *c, int32_t B, int32_t k, const int32_t *draft, const int32_t *target_ids,
+                       const int32_t *force_len, int32_t *accept_len, int32_t *out_tokens, int32_t *kv_len,
+                       int32_t *pending, int32_t *n_new, int32_t *cu_new, void *stream) {
+  if (!c || B < 1 || k < 0 || k > 15) return SF_EINVAL;
+  if (!target_ids || !accept_len || !out_tokens || !kv_len || !pending || !n_new || !cu_new) return SF_EINVAL;
+  if (k > 0 && !draft && !force_len) return SF_EINVAL;
+  Run r{c, (hipStream_t)stream};
+  AcceptArgs a{target_ids, draft, force_len, accept_len, out_tokens, kv_len, pending, n_new, cu_new, B, k};
   LAUNCH(K_ACCEPT, launch_accept(a, r.s));
   return r.st;
 }
@@ -523,15 +607,15 @@ size_t sf_linear_workspace_bytes(const sf_ctx *c, int32_t M) {
   return gemm_workspace_bytes(M);
 }
 
-sf_status sf_tune_attention(int32_t chunk_tiles) {
-  if (chunk_tiles < 0 || (chunk_tiles > 0 && chunk_tiles < 16)) return SF_EINVAL;
-  attn_tune(chunk_tiles);
+sf_status sf_tune_attention(sf_ctx *c, int32_t chunk_tiles) {
+  if (!c || chunk_tiles < 0 || (chunk_tiles > 0 && chunk_tiles < 16)) return SF_EINVAL;
+  c->tune_chunk = chunk_tiles;
   return SF_OK;
 }
 
-sf_status sf_tune_linear(int32_t tile, int32_t split_k) {
-  if (tile < 0 || tile > gemm_num_tiles() || split_k < 0 || split_k > 64) return SF_EINVAL;
-  gemm_tune(tile, split_k);
+sf_status sf_tune_linear(sf_ctx *c, int32_t tile, int32_t split_k) {
+  if (!c || tile < 0 || tile > gemm_num_tiles() || split_k < 0 || split_k > 64) return SF_EINVAL;
+  c->tune_tile = tile; c->tune_split = split_k;
   return SF_OK;
 }
 
@@ -555,6 +639,32 @@ sf_status sf_op_linear(const sf_ctx *c, const void *x, const void *w, const void
   Run r{c, (hipStream_t)stream};
   r.gemm_ws = workspace; r.gemm_ws_bytes = workspace ? workspace_bytes : 0;
   gemm(r, c->tc.dtype, x, w, bias, residual, y, M, N, K, out_f32);
+  return r.st;
+}
+
+size_t sf_linear_argmax_workspace_bytes(const sf_ctx *c, int32_t M, int32_t N) {
+  if (!c || M < 1 || N < 1) return 0;
+  const bool bf = c->tc.dtype == SF_BF16;
+  const size_t parts = bf ? (size_t)gemm_argmax_parts(N) : (size_t)ARGMAX_SEGS;
+  return up(bf ? gemm_workspace_bytes(M) : 0) + 2 * up((size_t)M * parts * 4) + up(bf ? 0 : (size_t)M * N * sizeof(float));
+}
+
+sf_status sf_op_linear_argmax(const sf_ctx *c, const void *x, const void *w, int32_t M, int32_t N, int32_t K,
+                              int32_t *ids, float *logits, void *workspace, size_t workspace_bytes, void *stream) {
+  if (!c || !x || !w || !ids || !workspace || M < 1 || N < 1 || K < 1) return SF_EINVAL;
+  if (K % 8 || N % 8) return SF_EUNSUPPORTED;
+  if (((uintptr_t)x | (uintptr_t)w) % 16 || ((uintptr_t)workspace) % ALIGN) return SF_EINVAL;
+  if (workspace_bytes < sf_linear_argmax_workspace_bytes(c, M, N)) return SF_ECAPACITY;
+  const bool bf = c->tc.dtype == SF_BF16;
+  const size_t parts = bf ? (size_t)gemm_argmax_parts(N) : (size_t)ARGMAX_SEGS;
+  char *ws = (char *)workspace;
+  const size_t lin = up(bf ? gemm_workspace_bytes(M) : 0), pb = up((size_t)M * parts * 4);
+  sf_model_cfg m = c->tc;
+  m.vocab = N; m.d_model = K;
+  Run r{c, (hipStream_t)stream};
+  if (bf) { r.gemm_ws = ws; r.gemm_ws_bytes = lin; }
+  lm_head_argmax(r, m, x, w, logits, (float *)(ws + lin + 2 * pb), (float *)(ws + lin), (int32_t *)(ws + lin + pb), ids,
+                 M);
   return r.st;
 }
 
@@ -664,7 +774,7 @@ sf_status sf_op_argmax(const sf_ctx *c, const float *logits, int32_t M, int32_t 
   int32_t *pidx = (int32_t *)((char *)workspace + up((size_t)M * ARGMAX_SEGS * sizeof(float)));
   Run r{c, (hipStream_t)stream};
   LAUNCH(K_ARGMAX, launch_argmax_partial(logits, M, V, pmax, pidx, r.s));
-  LAUNCH(K_ACCEPT, launch_argmax_final(pmax, pidx, M, ids, r.s));
+  LAUNCH(K_ACCEPT, launch_argmax_final(pmax, pidx, M, ARGMAX_SEGS, ARGMAX_SEGS, ids, r.s));
   return r.st;
 }
 
@@ -703,7 +813,7 @@ const char *sf_strerror(sf_status s) {
     case SF_OK: return "ok";
     case SF_EINVAL: return "invalid argument";
     case SF_ECAPACITY: return "capacity exceeded (cache or workspace too small)";
-    case SF_ESTATE: return "call order: weights not bound";
+    case SF_ESTATE: return "call order: weights not bound, or no verified block to commit";
     case SF_EHIP: return "HIP error";
     case SF_EUNSUPPORTED: return "shape not supported by the kernels";
   }

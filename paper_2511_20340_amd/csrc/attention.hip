@@ -378,15 +378,11 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
 
 }  // namespace
 
-namespace { int g_chunk_tiles = 0; }
-void attn_tune(int chunk_tiles) { g_chunk_tiles = chunk_tiles; }
-
 // Chunk size (in 32-key tiles) of the split-KV decomposition.  The grid is sized from the host's
 // upper bound of the lengths: split only when there are fewer (sequence, head, row tile) groups
 // than CUs, and never below 16 tiles (4 per wave) per chunk; with >= 256 groups every group is one
 // workgroup and no combine pass is needed (measured fastest at every batch >= 32).
 int attn_chunk_tiles(int groups, int keys_upper) {
-  if (g_chunk_tiles > 0) return g_chunk_tiles;
   const int n_tiles = (keys_upper + TK - 1) / TK;
   const int want_chunks = (256 + groups - 1) / (groups > 0 ? groups : 1);
   int ct = (n_tiles + want_chunks - 1) / want_chunks;

@@ -16,10 +16,9 @@ __device__ __forceinline__ float block_sum_256(float v, float *red) {
   return t;
 }
 
-// 16-byte vector access to a row of T: VEC elements per access
-template <typename T> struct Vec;
-template <> struct Vec<bf16_t> {
-  static constexpr int N = 8;
+// 8 consecutive elements of a row of T, as floats
+template <typename T> struct Vec8;
+template <> struct Vec8<bf16_t> {
   static __device__ __forceinline__ void ld(const bf16_t *p, float (&v)[8]) {
     const uint4 u = *reinterpret_cast<const uint4 *>(p);
     const uint32_t w[4] = {u.x, u.y, u.z, u.w};
@@ -31,26 +30,26 @@ template <> struct Vec<bf16_t> {
                                                pack2bf(v[6], v[7]));
   }
 };
-template <> struct Vec<float> {
-  static constexpr int N = 4;
-  static __device__ __forceinline__ void ld(const float *p, float (&v)[4]) {
-    const float4 u = *reinterpret_cast<const float4 *>(p);
-    v[0] = u.x; v[1] = u.y; v[2] = u.z; v[3] = u.w;
+template <> struct Vec8<float> {
+  static __device__ __forceinline__ void ld(const float *p, float (&v)[8]) {
+    const float4 a = *reinterpret_cast<const float4 *>(p), b = *reinterpret_cast<const float4 *>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
   }
-  static __device__ __forceinline__ void st(float *p, const float (&v)[4]) {
+  static __device__ __forceinline__ void st(float *p, const float (&v)[8]) {
     *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4 *>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
   }
 };
 
-// One workgroup per output row.  y = gain[r % n_gain] * x / sqrt(mean(x^2) + eps).
-// The row stays in registers between the two passes (up to 4 x 16 bytes per thread, i.e.
-// d <= 8192 bf16 / 4096 fp32); longer or unaligned rows take the scalar path.
-template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const T *__restrict__ X, const T *__restrict__ gain,
-                                                      T *__restrict__ Y, int d, int n_gain, float eps, int map,
+// One workgroup per output row.  y = gain[r % n_gain] * x / sqrt(mean(x^2) + eps).  TI: type of x (float for
+// rows of the residual stream), TO: type of the gains and of y.
+// The row stays in registers between the two passes (up to 4 x 8 elements per thread, i.e. d <= 8192);
+// longer or unaligned rows take the scalar path.
+template <typename TI, typename TO>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const TI *__restrict__ X, const TO *__restrict__ gain,
+                                                      TO *__restrict__ Y, int d, int n_gain, float eps, int map,
                                                       int q, int q_max, const int32_t *__restrict__ n_new) {
   __shared__ float red[4];
-  constexpr int VN = Vec<T>::N;
   const int r = blockIdx.x;
   long in_row = r;
   bool zero = false;
@@ -64,35 +63,35 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *__restrict__ X, c
   } else if (map == 3) {  // row r itself, silenced when sequence r committed nothing
     zero = n_new[r] <= 0;
   }
-  const T *x = X + in_row * d;
-  const T *gv = gain + (size_t)(r % n_gain) * d;
-  T *y = Y + (size_t)r * d;
-  if (d % VN == 0 && d <= VN * 256 * 4) {
-    float v[4][VN];
+  const TI *x = X + in_row * d;
+  const TO *gv = gain + (size_t)(r % n_gain) * d;
+  TO *y = Y + (size_t)r * d;
+  if (d % 8 == 0 && d <= 8 * 256 * 4) {
+    float v[4][8];
     float ss = 0.f;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int e = (threadIdx.x + 256 * j) * VN;
+      const int e = (threadIdx.x + 256 * j) * 8;
       if (e < d && !zero) {
-        Vec<T>::ld(x + e, v[j]);
+        Vec8<TI>::ld(x + e, v[j]);
 #pragma unroll
-        for (int i = 0; i < VN; ++i) ss += v[j][i] * v[j][i];
+        for (int i = 0; i < 8; ++i) ss += v[j][i] * v[j][i];
       } else {
 #pragma unroll
-        for (int i = 0; i < VN; ++i) v[j][i] = 0.f;
+        for (int i = 0; i < 8; ++i) v[j][i] = 0.f;
       }
     }
     ss = block_sum_256(ss, red);
     const float inv = 1.0f / sqrtf(ss / (float)d + eps);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int e = (threadIdx.x + 256 * j) * VN;
+      const int e = (threadIdx.x + 256 * j) * 8;
       if (e < d) {
-        float g[VN], o[VN];
-        Vec<T>::ld(gv + e, g);
+        float g[8], o[8];
+        Vec8<TO>::ld(gv + e, g);
 #pragma unroll
-        for (int i = 0; i < VN; ++i) o[i] = g[i] * (v[j][i] * inv);
-        Vec<T>::st(y + e, o);
+        for (int i = 0; i < 8; ++i) o[i] = g[i] * (v[j][i] * inv);
+        Vec8<TO>::st(y + e, o);
       }
     }
     return;
@@ -100,14 +99,14 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *__restrict__ X, c
   float ss = 0.f;
   if (!zero)
     for (int e = threadIdx.x; e < d; e += 256) {
-      const float v = Elem<T>::ld(x + e);
+      const float v = Elem<TI>::ld(x + e);
       ss += v * v;
     }
   ss = block_sum_256(ss, red);
   const float inv = 1.0f / sqrtf(ss / (float)d + eps);
   for (int e = threadIdx.x; e < d; e += 256) {
-    const float v = zero ? 0.f : Elem<T>::ld(x + e);
-    Elem<T>::st(y + e, Elem<T>::ld(gv + e) * (v * inv));
+    const float v = zero ? 0.f : Elem<TI>::ld(x + e);
+    Elem<TO>::st(y + e, Elem<TO>::ld(gv + e) * (v * inv));
   }
 }
 
@@ -205,18 +204,27 @@ __global__ void silu_mul_kernel(const float *__restrict__ gu, T *__restrict__ ac
   Elem<T>::st(act + idx, g / (1.0f + expf(-g)) * u);
 }
 
-// h[row] = embed[token(row)], also stored as hooked state 0.  Out-of-range ids read row 0.
+// h[row] = embed[token(row)] as float (the residual stream), hb its copy in the model dtype (optional), and
+// the same row as hooked state g for every group g in hook_mask.  Out-of-range ids read row 0.
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const T *__restrict__ E, const int32_t *__restrict__ pending,
-                                                    const int32_t *__restrict__ draft, T *__restrict__ H,
-                                                    T *__restrict__ hooks, int k, int q_max, int d, int vocab) {
+                                                    const int32_t *__restrict__ draft, float *__restrict__ H,
+                                                    T *__restrict__ Hb, T *__restrict__ hooks, int hook_mask, int k,
+                                                    int q_max, int d, int vocab) {
   const int row = blockIdx.x, q = k + 1, b = row / q, i = row % q;
   int tok = i == 0 ? pending[b] : draft[b * k + i - 1];
   if (tok < 0 || tok >= vocab) tok = 0;
   const T *src = E + (size_t)tok * d;
-  T *h = H + (size_t)row * d;
-  T *hk = hooks + (((size_t)b * q_max + i) * 4 + 0) * d;
-  for (int e = threadIdx.x; e < d; e += 256) { const T v = src[e]; h[e] = v; hk[e] = v; }
+  float *h = H + (size_t)row * d;
+  T *hk = hooks + ((size_t)b * q_max + i) * 4 * d;
+  for (int e = threadIdx.x; e < d; e += 256) {
+    const T v = src[e];
+    h[e] = Elem<T>::ld(&v);
+    if (Hb) Hb[(size_t)row * d + e] = v;
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      if (hook_mask >> g & 1) hk[(size_t)g * d + e] = v;
+  }
 }
 
 // The newest committed context row of every sequence, raw (the residual input of the context
@@ -233,12 +241,12 @@ __global__ __launch_bounds__(256) void gather_last_kernel(const T *__restrict__ 
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void hook_copy_kernel(const T *__restrict__ H, T *__restrict__ hooks, int q,
+__global__ __launch_bounds__(256) void hook_copy_kernel(const float *__restrict__ H, T *__restrict__ hooks, int q,
                                                         int q_max, int d, int group) {
   const int row = blockIdx.x, b = row / q, i = row % q;
-  const T *h = H + (size_t)row * d;
+  const float *h = H + (size_t)row * d;
   T *hk = hooks + (((size_t)b * q_max + i) * 4 + group) * d;
-  for (int e = threadIdx.x; e < d; e += 256) hk[e] = h[e];
+  for (int e = threadIdx.x; e < d; e += 256) Elem<T>::st(hk + e, h[e]);
 }
 
 // plain [B][Hkv][cap][hd] <-> tiled (bf16) / plain (fp32: straight copy)
@@ -266,10 +274,10 @@ __global__ __launch_bounds__(256) void calib_copy_kernel(const uint4 *__restrict
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
-template <typename T>
+template <typename TI, typename TO>
 hipError_t rmsnorm_t(const NormArgs &a, hipStream_t s) {
-  rmsnorm_kernel<T><<<a.M, 256, 0, s>>>((const T *)a.x, (const T *)a.gain, (T *)a.y, a.d, a.n_gain, a.eps, a.map,
-                                        a.q, a.q_max, a.n_new);
+  rmsnorm_kernel<TI, TO><<<a.M, 256, 0, s>>>((const TI *)a.x, (const TO *)a.gain, (TO *)a.y, a.d, a.n_gain, a.eps,
+                                             a.map, a.q, a.q_max, a.n_new);
   return hipGetLastError();
 }
 
@@ -289,7 +297,8 @@ hipError_t launch_calib_copy(const void *src, void *dst, size_t bytes, hipStream
 }
 
 hipError_t launch_rmsnorm(const NormArgs &a, int dtype, hipStream_t s) {
-  return dtype == SF_BF16 ? rmsnorm_t<bf16_t>(a, s) : rmsnorm_t<float>(a, s);
+  if (dtype != SF_BF16) return rmsnorm_t<float, float>(a, s);
+  return a.x_f32 ? rmsnorm_t<float, bf16_t>(a, s) : rmsnorm_t<bf16_t, bf16_t>(a, s);
 }
 
 hipError_t launch_rope_table(const RopeArgs &a, hipStream_t s) {
@@ -312,15 +321,16 @@ hipError_t launch_silu_mul(const float *gu, void *act, int M, int F, int dtype, 
   return hipGetLastError();
 }
 
-hipError_t launch_embed(const void *embed, const int32_t *pending, const int32_t *draft, void *h, void *hooks,
-                        int B, int k, int q_max, int d, int vocab, int dtype, hipStream_t s) {
+hipError_t launch_embed(const void *embed, const int32_t *pending, const int32_t *draft, float *h, void *hb,
+                        void *hooks, int hook_mask, int B, int k, int q_max, int d, int vocab, int dtype,
+                        hipStream_t s) {
   const int M = B * (k + 1);
   if (dtype == SF_BF16)
-    embed_kernel<bf16_t><<<M, 256, 0, s>>>((const bf16_t *)embed, pending, draft, (bf16_t *)h, (bf16_t *)hooks, k,
-                                           q_max, d, vocab);
+    embed_kernel<bf16_t><<<M, 256, 0, s>>>((const bf16_t *)embed, pending, draft, h, (bf16_t *)hb, (bf16_t *)hooks,
+                                           hook_mask, k, q_max, d, vocab);
   else
-    embed_kernel<float><<<M, 256, 0, s>>>((const float *)embed, pending, draft, (float *)h, (float *)hooks, k,
-                                          q_max, d, vocab);
+    embed_kernel<float><<<M, 256, 0, s>>>((const float *)embed, pending, draft, h, nullptr, (float *)hooks,
+                                          hook_mask, k, q_max, d, vocab);
   return hipGetLastError();
 }
 
@@ -333,12 +343,10 @@ hipError_t launch_gather_last(const void *x, void *out, const int32_t *n_new, co
   return hipGetLastError();
 }
 
-hipError_t launch_hook_copy(const void *h, void *hooks, int B, int q, int q_max, int d, int group, int dtype,
+hipError_t launch_hook_copy(const float *h, void *hooks, int B, int q, int q_max, int d, int group, int dtype,
                             hipStream_t s) {
-  if (dtype == SF_BF16)
-    hook_copy_kernel<bf16_t><<<B * q, 256, 0, s>>>((const bf16_t *)h, (bf16_t *)hooks, q, q_max, d, group);
-  else
-    hook_copy_kernel<float><<<B * q, 256, 0, s>>>((const float *)h, (float *)hooks, q, q_max, d, group);
+  if (dtype == SF_BF16) hook_copy_kernel<bf16_t><<<B * q, 256, 0, s>>>(h, (bf16_t *)hooks, q, q_max, d, group);
+  else hook_copy_kernel<float><<<B * q, 256, 0, s>>>(h, (float *)hooks, q, q_max, d, group);
   return hipGetLastError();
 }
 

@@ -28,6 +28,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdint>
 
 namespace sf {
 namespace {
@@ -35,6 +36,31 @@ namespace {
 constexpr int BK = 64;
 constexpr int LDK = 72;  // padded LDS row length in bf16 elements (144 B)
 constexpr int XCDS = 8;
+
+// Where a workgroup's finished accumulators go.
+struct Epilogue {
+  const bf16_t *bias;    // [N] or null
+  const void *residual;  // [M][N] bf16, or float when res_f32; may alias y
+  void *y;               // [M][N] bf16, or float when out_f32; null: not stored (arg-max partials only)
+  bf16_t *y2;            // optional bf16 copy of y
+  bf16_t *hooks;         // optional: bf16 copies of block row (r / hook_q, r % hook_q) into the groups of hook_mask
+  float *am_val;         // optional [M][am_stride]: per row and column tile the largest value ...
+  int32_t *am_idx;       // ... and its column
+  int hook_mask, hook_q, hook_qmax, am_stride;
+  int out_f32, res_f32, glu;
+};
+
+// max over the 32 lanes that share (lane >> 5): quad permutes, the two row mirrors, one cross-row exchange.
+// maxNum semantics: a NaN operand is ignored.
+__device__ __forceinline__ float half_wave_max(float v) {
+#define SF_DPP(x, ctrl) __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), ctrl, 0xf, 0xf, false))
+  v = fmaxf(v, SF_DPP(v, 0xB1));   // quad_perm [1,0,3,2]
+  v = fmaxf(v, SF_DPP(v, 0x4E));   // quad_perm [2,3,0,1]
+  v = fmaxf(v, SF_DPP(v, 0x141));  // row_half_mirror: quads of an 8-lane group
+  v = fmaxf(v, SF_DPP(v, 0x140));  // row_mirror: the two 8-lane groups of a 16-lane row
+#undef SF_DPP
+  return fmaxf(v, __shfl_xor(v, 16));
+}
 
 // What every bf16 kernel variant does once a workgroup holds its accumulators: the split-K hand-over
 // (partials, ticket, ordered sum in the last workgroup to arrive) and the output epilogue.
@@ -44,20 +70,22 @@ constexpr int XCDS = 8;
 // workgroup's K range in sS[BM]; the row factor 1/sqrt(mean(x^2)+eps) commutes with the K sum and
 // is applied to the accumulators here.  With split-K the per-split sums travel next to the partial
 // tiles and are added in split order too.
+//
+// scratch: LDS the main loop no longer needs, at least NW * BM * 8 bytes (arg-max partials).
 template <int TM, int TN, int NW = 4>
-__device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const bf16_t *__restrict__ bias,
-                                            const bf16_t *residual, void *Y, int M, int N, int out_f32, int tiles_m,
+__device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const Epilogue &e, int M, int N, int tiles_m,
                                             int split_k, float *__restrict__ partial,
-                                            unsigned *__restrict__ tickets, int glu, int tm, int tn, int ks, int m0,
-                                            int nb0, unsigned &s_ticket, float *sS = nullptr,
+                                            unsigned *__restrict__ tickets, int tm, int tn, int ks, int m0,
+                                            int nb0, unsigned &s_ticket, void *scratch, float *sS = nullptr,
                                             float *__restrict__ ssq_part = nullptr, int K = 1, float eps = 0.f) {
   constexpr int BM = TM * 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
   if (split_k > 1) {
-    // Partial tiles in register order: [tile][split][wave][TM][TN][reg][lane].  They are written
-    // and read with agent-scope accesses (write-through / cache-bypassing), so no L2-wide
-    // writeback or invalidate is needed to make them visible to the workgroup that finishes.
+    // Partial tiles in register order: [tile][split][wave][TM][TN][reg][lane], written and read with
+    // agent-scope accesses.  Hand-over: every wave releases its stores at agent scope, the workgroup
+    // meets at a barrier, one thread takes the tile's ticket (acquire-release, agent scope); the
+    // workgroup that draws the last ticket acquires at agent scope before it reads the other splits.
     const size_t tile = (size_t)tn * tiles_m + tm;
     constexpr size_t PER_WAVE = (size_t)TM * TN * 64 * 16;
     float *mine = partial + ((tile * split_k + ks) * NW + wave) * PER_WAVE;
@@ -72,11 +100,12 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const bf16_t 
     if (sS && tid < BM)
       __hip_atomic_store(ssq_part + (tile * split_k + ks) * BM + tid, sS[tid], __ATOMIC_RELAXED,
                          __HIP_MEMORY_SCOPE_AGENT);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's stores have been acknowledged
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
     __syncthreads();
-    if (tid == 0) s_ticket = __hip_atomic_fetch_add(&tickets[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) s_ticket = __hip_atomic_fetch_add(&tickets[tile], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (s_ticket != (unsigned)(split_k - 1)) return;  // not the last split of this tile
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 #pragma unroll
     for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -120,7 +149,7 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const bf16_t 
       }
   }
 
-  if (glu) {
+  if (e.glu) {
     // SwiGLU epilogue.  The weight was packed with gate and up rows interleaved 16 by 16, so a
     // 32-column tile holds gate features f..f+15 in columns 0-15 and the matching up features in
     // columns 16-31: lane ln < 16 fetches its partner's value and writes silu(gate) * up.
@@ -137,11 +166,58 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const bf16_t 
           const int row = m0 + a * 32 + c_row(v, lh);
           if ((ln & 16) == 0 && col < F && row < M) {
             const float r = mine / (1.0f + __expf(-mine)) * other;
-            reinterpret_cast<bf16_t *>(Y)[(size_t)row * F + col] = f2bf(r);
+            reinterpret_cast<bf16_t *>(e.y)[(size_t)row * F + col] = f2bf(r);
           }
         }
       }
     return;
+  }
+
+  if (e.am_val) {
+    // Arg-max partials of this workgroup's column tile: per row the largest accumulator and the lowest
+    // column that holds it.  Columns past N and NaN never take part.
+    float *s_val = reinterpret_cast<float *>(scratch);       // [NW][BM]
+    int32_t *s_idx = reinterpret_cast<int32_t *>(s_val + NW * BM);
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        float best_v = -__builtin_huge_valf();
+        int32_t best_i = INT32_MAX;
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+          const int col = (nb0 + b) * 32 + ln;
+          const float x = col < N ? acc[a][b][v] : -__builtin_huge_valf();
+          const float mx = half_wave_max(x);
+          const unsigned long long bal = __ballot(col < N && x == mx);
+          const uint32_t half = lh ? (uint32_t)(bal >> 32) : (uint32_t)bal;
+          if (half != 0 && mx > best_v) {  // later blocks hold higher columns: strictly greater only
+            best_v = mx;
+            best_i = (nb0 + b) * 32 + (__ffs(half) - 1);
+          } else if (half != 0 && best_i == INT32_MAX) {  // a tile of -inf only: its first column
+            best_v = mx;
+            best_i = (nb0 + b) * 32 + (__ffs(half) - 1);
+          }
+        }
+        if (ln == 0) {
+          s_val[wave * BM + a * 32 + c_row(v, lh)] = best_v;
+          s_idx[wave * BM + a * 32 + c_row(v, lh)] = best_i;
+        }
+      }
+    __syncthreads();
+    if (tid < BM && m0 + tid < M) {
+      float bv = s_val[tid];
+      int32_t bi = s_idx[tid];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) {  // waves hold ascending column ranges
+        const float v = s_val[w * BM + tid];
+        const int32_t i = s_idx[w * BM + tid];
+        if (i != INT32_MAX && (bi == INT32_MAX || v > bv)) { bv = v; bi = i; }
+      }
+      e.am_val[(size_t)(m0 + tid) * e.am_stride + tn] = bv;
+      e.am_idx[(size_t)(m0 + tid) * e.am_stride + tn] = bi;
+    }
+    if (!e.y) return;
   }
 
   // epilogue: lane holds column ln, rows c_row(v, lh) of every 32x32 tile.  y may be the residual
@@ -153,13 +229,15 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const bf16_t 
     for (int b = 0; b < TN; ++b) {
       const int col = (nb0 + b) * 32 + ln;
       if (col >= N) continue;
-      const float bv = bias ? bf2f(bias[col]) : 0.f;
-      bf16_t res[16];
-      if (residual) {
+      const float bv = e.bias ? bf2f(e.bias[col]) : 0.f;
+      float res[16];
+      if (e.residual) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int row = min(m0 + a * 32 + c_row(v, lh), M - 1);
-          res[v] = residual[(size_t)row * N + col];
+          const size_t o = (size_t)row * N + col;
+          res[v] = e.res_f32 ? reinterpret_cast<const float *>(e.residual)[o]
+                             : bf2f(reinterpret_cast<const bf16_t *>(e.residual)[o]);
         }
       }
 #pragma unroll
@@ -168,9 +246,16 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const bf16_t 
         if (row >= M) continue;
         float r = acc[a][b][v] + bv;
         const size_t o = (size_t)row * N + col;
-        if (residual) r += bf2f(res[v]);
-        if (out_f32) reinterpret_cast<float *>(Y)[o] = r;
-        else reinterpret_cast<bf16_t *>(Y)[o] = f2bf(r);
+        if (e.residual) r += res[v];
+        if (e.out_f32) reinterpret_cast<float *>(e.y)[o] = r;
+        else reinterpret_cast<bf16_t *>(e.y)[o] = f2bf(r);
+        if (e.y2) e.y2[o] = f2bf(r);
+        if (e.hooks) {
+          const size_t hrow = ((size_t)(row / e.hook_q) * e.hook_qmax + row % e.hook_q) * 4;
+#pragma unroll
+          for (int g = 1; g < 4; ++g)
+            if (e.hook_mask >> g & 1) e.hooks[(hrow + g) * N + col] = f2bf(r);
+        }
       }
     }
 }
@@ -180,12 +265,10 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const bf16_t 
 // slices, and slices past the workgroup's K range contribute zeros.
 template <int TM, int TN, int R, int OCC, int NW, int NORM>
 __global__ __launch_bounds__(64 * NW, OCC) void gemm_ring_kernel(const bf16_t *__restrict__ A,
-                                                        const uint4 *__restrict__ Wp,
-                                                        const bf16_t *__restrict__ bias, const bf16_t *residual,
-                                                        void *Y, int M, int N, int K, int out_f32, int tiles_m,
-                                                        int tiles_n, int split_k, int kt_per_split,
-                                                        float *__restrict__ partial,
-                                                        unsigned *__restrict__ tickets, int glu, float eps,
+                                                        const uint4 *__restrict__ Wp, const Epilogue e, int M,
+                                                        int N, int K, int tiles_m, int tiles_n, int split_k,
+                                                        int kt_per_split, float *__restrict__ partial,
+                                                        unsigned *__restrict__ tickets, float eps,
                                                         float *__restrict__ ssq_part) {
   static_assert(R >= 2, "the slot after the current one holds the next activation chunk");
   constexpr int BM = TM * 32;
@@ -310,8 +393,8 @@ __global__ __launch_bounds__(64 * NW, OCC) void gemm_ring_kernel(const bf16_t *_
     }
     __syncthreads();
   }
-  gemm_finish<TM, TN, NW>(acc, bias, residual, Y, M, N, out_f32, tiles_m, split_k, partial, tickets, glu, tm, tn, ks, m0, nb0,
-                      s_ticket, NORM ? sS : nullptr, ssq_part, K, eps);
+  gemm_finish<TM, TN, NW>(acc, e, M, N, tiles_m, split_k, partial, tickets, tm, tn, ks, m0, nb0, s_ticket, sA,
+                          NORM ? sS : nullptr, ssq_part, K, eps);
 }
 
 // row-major [N][K] -> packed units; one thread per 16-byte operand register
@@ -387,16 +470,20 @@ hipError_t run_ring(const GemmArgs &a, hipStream_t s, int split, int mode) {
   float *ssq_part = a.ws ? (float *)((char *)a.ws + GEMM_TICKET_BYTES) : nullptr;
   float *partial = a.ws ? (float *)((char *)a.ws + GEMM_TICKET_BYTES + GEMM_SSQ_BYTES) : nullptr;
   const dim3 grid(groups * XCDS * p.tiles_m * p.split_k), block(64 * NW);
+  if (a.am_val && (p.split_k != 1 || a.am_stride < p.tiles_n)) return hipErrorInvalidValue;
+  if (a.am_val && a.am_parts_out) *a.am_parts_out = p.tiles_n;
+  static_assert((size_t)2 * BM * LDK * sizeof(bf16_t) >= (size_t)NW * BM * 8, "arg-max partials fit the activation tile");
+  const Epilogue e{(const bf16_t *)a.bias, a.residual, a.y, (bf16_t *)a.y2, (bf16_t *)a.hooks, a.am_val, a.am_idx,
+                   a.hook_mask, a.hook_q, a.hook_qmax, a.am_stride, a.out_f32, a.res_f32, a.glu};
   if (a.fused_norm) {
     lds += (size_t)BM * sizeof(float);
     gemm_ring_kernel<TM, TN, R, OCC, NW, 1><<<grid, block, lds, s>>>(
-        (const bf16_t *)a.x, (const uint4 *)a.w, (const bf16_t *)a.bias, (const bf16_t *)a.residual, a.y, a.M, a.N,
-        a.K, a.out_f32, p.tiles_m, p.tiles_n, p.split_k, p.kt_per_split, partial, tickets, a.glu, a.norm_eps,
-        ssq_part);
+        (const bf16_t *)a.x, (const uint4 *)a.w, e, a.M, a.N, a.K, p.tiles_m, p.tiles_n, p.split_k, p.kt_per_split,
+        partial, tickets, a.norm_eps, ssq_part);
   } else {
     gemm_ring_kernel<TM, TN, R, OCC, NW, 0><<<grid, block, lds, s>>>(
-        (const bf16_t *)a.x, (const uint4 *)a.w, (const bf16_t *)a.bias, (const bf16_t *)a.residual, a.y, a.M, a.N,
-        a.K, a.out_f32, p.tiles_m, p.tiles_n, p.split_k, p.kt_per_split, partial, tickets, a.glu, 0.f, nullptr);
+        (const bf16_t *)a.x, (const uint4 *)a.w, e, a.M, a.N, a.K, p.tiles_m, p.tiles_n, p.split_k, p.kt_per_split,
+        partial, tickets, 0.f, nullptr);
   }
   return hipGetLastError();
 }
@@ -578,11 +665,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
     }
 }
 
-int g_tile = 0, g_split = 0;  // process-wide overrides for sweeps (0 = automatic)
-
 }  // namespace
 
-void gemm_tune(int tile, int split_k) { g_tile = tile; g_split = split_k; }
 int gemm_num_tiles() { return N_TILES; }
 int gemm_tile_rows(int tile) { return tile >= 1 && tile <= N_TILES ? TILE_TM[tile] * 32 : 0; }
 
@@ -617,14 +701,12 @@ hipError_t launch_pack_weight(const void *w, void *packed, int N, int K, int glu
 }
 
 hipError_t launch_gemm_bf16(const GemmArgs &a, hipStream_t s) {
-  GemmConfig c = {a.tile, a.split};
+  GemmConfig c = {a.tile, a.am_val ? 1 : a.split};  // arg-max partials: one workgroup owns a tile's whole K range
   if (c.tile <= 0 || c.split <= 0) {
     const GemmConfig h = gemm_heuristic(a.M, a.plan_M > 0 ? a.plan_M : a.M, a.N, a.K, a.ws ? a.ws_bytes : 0);
     if (c.split <= 0) c.split = h.split;
     if (c.tile <= 0) c.tile = c.split == h.split ? h.tile : pick(a.M, a.N, a.K, a.ws ? a.ws_bytes : 0, c.split).tile;
   }
-  if (g_tile > 0) c.tile = g_tile;
-  if (g_split > 0) c.split = g_split;
   return dispatch(c.tile, a, s, c.split, 0);
 }
 

@@ -82,7 +82,6 @@ struct AttnArgs {
   int n_chunks;     // grid.x
 };
 int attn_chunk_tiles(int groups, int keys_upper);  // groups = B * Hkv * row tiles
-void attn_tune(int chunk_tiles);                   // tuning override, 0 = automatic
 size_t attn_workspace_bytes(int B, int Hkv, int hd, int G, int n_q, int len_upper);
 hipError_t launch_attention_bf16(const AttnArgs &a, hipStream_t s);
 // merges the split-KV partials (only needed when a.n_chunks > 1)
@@ -104,7 +103,24 @@ struct GemmArgs {
   // folded into w's columns at pack time; the kernel supplies the row factor 1/sqrt(mean(x^2)+eps)
   int fused_norm = 0;
   float norm_eps = 0.f;
+  // bf16 only, the residual stream: residual (and with out_f32 the output) is float [M][N]; y2, when
+  // set, receives a bf16 copy of the output (what the next norm + linear pair multiplies with)
+  int res_f32 = 0;
+  void *y2 = nullptr;
+  // bf16 only: the output rows are block rows (b, i) = (row / hook_q, row % hook_q); their bf16 copy also
+  // goes to hooks[b][i][g][:] ([B][hook_qmax][4][N]) for every group g in hook_mask
+  void *hooks = nullptr;
+  int hook_mask = 0, hook_q = 1, hook_qmax = 1;
+  // bf16 only: per output row and column tile the largest value and its column (lowest on ties, NaN never
+  // wins, (-inf, INT_MAX) when the tile holds no comparable value): am_val/am_idx [M][am_stride], entry
+  // [row][column tile]; y may then be NULL (logits not materialised).  Forces split 1.
+  float *am_val = nullptr;
+  int32_t *am_idx = nullptr;
+  int am_stride = 0;
+  int *am_parts_out = nullptr;  // host: receives the number of column tiles the launch wrote partials for
 };
+// column tiles the arg-max partials of an N-column layer can have at most (narrowest tile: 128 columns)
+inline int gemm_argmax_parts(int N) { return (N + 127) / 128; }
 struct GemmConfig {
   int tile, split;
 };
@@ -112,7 +128,6 @@ constexpr size_t GEMM_TICKET_BYTES = 64 * 1024;
 constexpr size_t GEMM_PARTIAL_BYTES = 96u * 1024 * 1024;
 constexpr size_t GEMM_SSQ_BYTES = 1024 * 1024;  // split-K: per-split row sums of squares of the fused norm
 size_t gemm_workspace_bytes(int M_max);
-void gemm_tune(int tile, int split_k);  // tuning overrides, 0 = automatic
 int gemm_num_tiles();
 int gemm_tile_rows(int tile);
 GemmConfig gemm_heuristic(int M, int plan_M, int N, int K, size_t ws_bytes);
@@ -136,6 +151,7 @@ struct NormArgs {
   int map;
   int q, q_max;
   const int32_t *n_new;
+  int x_f32 = 0;  // x is float whatever the model dtype (rows of the residual stream)
 };
 hipError_t launch_rmsnorm(const NormArgs &a, int dtype, hipStream_t s);
 hipError_t launch_calib_copy(const void *src, void *dst, size_t bytes, hipStream_t s);
@@ -158,22 +174,26 @@ hipError_t launch_rope_table(const RopeArgs &a, hipStream_t s);
 hipError_t launch_rope_kv(const RopeArgs &a, int dtype, hipStream_t s);
 
 hipError_t launch_silu_mul(const float *gu, void *act, int M, int F, int dtype, hipStream_t s);
-hipError_t launch_embed(const void *embed, const int32_t *pending, const int32_t *draft, void *h, void *hooks,
-                        int B, int k, int q_max, int d, int vocab, int dtype, hipStream_t s);
+// h (float) = embedding rows of the block tokens; hb (bf16 mode, may be null) their bf16 copy; hooks
+// groups in hook_mask receive the rows too
+hipError_t launch_embed(const void *embed, const int32_t *pending, const int32_t *draft, float *h, void *hb,
+                        void *hooks, int hook_mask, int B, int k, int q_max, int d, int vocab, int dtype,
+                        hipStream_t s);
 // out[b] = x[b*q + n_new[b]-1] (zero row when n_new[b]==0); len_m1[b] = max(kv_len[b]-1, 0)
 hipError_t launch_gather_last(const void *x, void *out, const int32_t *n_new, const int32_t *kv_len, int32_t *len_m1,
                               int B, int q, int d, int dtype, hipStream_t s);
-hipError_t launch_hook_copy(const void *h, void *hooks, int B, int q, int q_max, int d, int group, int dtype,
+hipError_t launch_hook_copy(const float *h, void *hooks, int B, int q, int q_max, int d, int group, int dtype,
                             hipStream_t s);
 hipError_t launch_kv_convert(const void *src, void *dst, int is_v, int to_tiled, int B, int Hkv, int cap, int hd,
                              int dtype, hipStream_t s);
 
 constexpr int ARGMAX_SEGS = 16;
 hipError_t launch_argmax_partial(const float *logits, int M, int V, float *pmax, int32_t *pidx, hipStream_t s);
-hipError_t launch_argmax_final(const float *pmax, const int32_t *pidx, int M, int32_t *ids, hipStream_t s);
+// ids[row] = column of the best of the row's n_part partials pmax/pidx[row * stride + 0..n_part)
+hipError_t launch_argmax_final(const float *pmax, const int32_t *pidx, int M, int n_part, int stride, int32_t *ids,
+                               hipStream_t s);
 struct AcceptArgs {
-  const float *pmax;
-  const int32_t *pidx;
+  const int32_t *target_ids;  // [B][k+1] the target's greedy choice at every block row
   const int32_t *draft, *force_len;
   int32_t *accept_len, *out_tokens, *kv_len, *pending, *n_new, *cu_new;
   int B, k;

@@ -19,9 +19,10 @@ def _stream():
 
 
 class Engine:
-    def __init__(self, cfg, B, cap, max_k, device="cuda:0"):
+    def __init__(self, cfg, B, cap, max_k, device="cuda:0", share_caches=None):
         """cfg: dict(n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, dtype
-        ('bf16'|'f32'), rope_theta, rms_eps)."""
+        ('bf16'|'f32'), rope_theta, rms_eps).  share_caches: another engine of the same shape, batch and
+        capacity whose K/V cache buffers this one works on instead of allocating its own."""
         self.lib = sfb.lib()
         self.cfg = dict(cfg)
         self.B, self.cap, self.max_k = int(B), int(cap), int(max_k)
@@ -44,7 +45,12 @@ class Engine:
         db = self.lib.sf_kv_cache_bytes(self.ctx, 1, self.B, self.cap)
         assert tb and db
         z = lambda nbytes: torch.zeros(nbytes // es, dtype=self.tdtype, device=self.dev)
-        self.tk, self.tv, self.dk, self.dv = z(tb), z(tb), z(db), z(db)
+        if share_caches is not None:
+            o = share_caches
+            assert (o.B, o.cap, o.cfg) == (self.B, self.cap, self.cfg) and o.tk.numel() * es == tb
+            self.tk, self.tv, self.dk, self.dv = o.tk, o.tv, o.dk, o.dv
+        else:
+            self.tk, self.tv, self.dk, self.dv = z(tb), z(tb), z(db), z(db)
         self.layer_elems = db // es
         i32 = dict(dtype=torch.int32, device=self.dev)
         self.kv_len = torch.zeros(self.B, **i32)
@@ -163,23 +169,42 @@ class Engine:
                                          _ptr(logits_out), _stream()), "sf_draft_step", self.ctx)
         return out
 
-    def sf_verify_step(self, k, draft, logits_out=None):
-        lg = logits_out if logits_out is not None else \
-            torch.empty(self.B, k + 1, self.V, dtype=torch.float32, device=self.dev)
+    def sf_verify_step(self, k, draft, logits_out=None, ids_out=None, logits=True):
+        """-> (logits [B,k+1,V] float32 or None, target_ids [B,k+1] int32).  logits=False asks for the
+        target's choices only: the logits are then not stored at all (bf16 mode)."""
+        lg = logits_out
+        if lg is None and logits:
+            lg = torch.empty(self.B, k + 1, self.V, dtype=torch.float32, device=self.dev)
+        ids = ids_out if ids_out is not None else torch.empty(self.B, k + 1, dtype=torch.int32, device=self.dev)
         sfb.check(self.lib.sf_verify_step(self.ctx, C.byref(self.st), k, _ptr(draft) if k > 0 else None,
-                                          self.len_upper, _ptr(lg), _stream()), "sf_verify_step", self.ctx)
-        return lg
+                                          self.len_upper, _ptr(lg), _ptr(ids), _stream()), "sf_verify_step", self.ctx)
+        return lg, ids
 
-    def sf_accept_commit(self, k, draft, logits, force_len=None, accept_out=None, tokens_out=None):
+    def sf_accept_commit(self, k, draft, target_ids, force_len=None, accept_out=None, tokens_out=None):
         acc = accept_out if accept_out is not None else torch.empty(self.B, dtype=torch.int32, device=self.dev)
         out = tokens_out if tokens_out is not None else \
             torch.empty(self.B, k + 1, dtype=torch.int32, device=self.dev)
         sfb.check(self.lib.sf_accept_commit(self.ctx, C.byref(self.st), k, _ptr(draft) if k > 0 else None,
-                                            _ptr(logits), _ptr(force_len), _ptr(acc), _ptr(out), _stream()),
+                                            _ptr(target_ids), _ptr(force_len), _ptr(acc), _ptr(out), _stream()),
                   "sf_accept_commit", self.ctx)
         if not self._pinned:
             self.len_upper = min(self.len_upper + k + 1, self.cap)
         return acc, out
+
+    def sf_op_accept(self, k, draft, target_ids, force_len=None):
+        """The acceptance rule alone on this engine's state arrays (no call-order check)."""
+        acc = torch.empty(self.B, dtype=torch.int32, device=self.dev)
+        out = torch.empty(self.B, k + 1, dtype=torch.int32, device=self.dev)
+        sfb.check(self.lib.sf_op_accept(self.ctx, self.B, k, _ptr(draft) if k > 0 else None, _ptr(target_ids),
+                                        _ptr(force_len), _ptr(acc), _ptr(out), _ptr(self.kv_len), _ptr(self.pending),
+                                        _ptr(self.n_new), _ptr(self.cu_new), _stream()), "sf_op_accept", self.ctx)
+        return acc, out
+
+    def sf_tune_linear(self, tile=0, split_k=0):
+        sfb.check(self.lib.sf_tune_linear(self.ctx, tile, split_k), "sf_tune_linear")
+
+    def sf_tune_attention(self, chunk_tiles=0):
+        sfb.check(self.lib.sf_tune_attention(self.ctx, chunk_tiles), "sf_tune_attention")
 
     def sf_profile_begin(self):
         sfb.check(self.lib.sf_profile_begin(self.ctx), "sf_profile_begin")
@@ -307,6 +332,25 @@ class Engine:
         self._pk_keep = pk
         return act
 
+    def sf_op_linear_argmax(self, x, w=None, packed=None, want_logits=False):
+        """ids [M] = argmax over the columns of x . w^T, as the LM head runs (+ the logits when asked for)."""
+        M, K = x.shape
+        if packed is None:
+            N = w.shape[0]
+            w = self.sf_pack_weight(w)
+            self._keep.pop()
+        else:
+            w, N = packed
+        nb = self.lib.sf_linear_argmax_workspace_bytes(self.ctx, M, N)
+        ws = torch.zeros(nb + 256, dtype=torch.uint8, device=self.dev)
+        p = ws.data_ptr() + (-ws.data_ptr()) % 256
+        ids = torch.empty(M, dtype=torch.int32, device=self.dev)
+        lg = torch.empty(M, N, dtype=torch.float32, device=self.dev) if want_logits else None
+        sfb.check(self.lib.sf_op_linear_argmax(self.ctx, _ptr(x), _ptr(w), M, N, K, _ptr(ids), _ptr(lg),
+                                               C.c_void_p(p), nb, _stream()), "sf_op_linear_argmax", self.ctx)
+        self._keep_ws = (ws, w)
+        return (ids, lg) if want_logits else ids
+
     def sf_op_rmsnorm(self, x, gain, n_gain=1):
         M, d = x.shape
         y = torch.empty_like(x)
@@ -386,8 +430,8 @@ class Engine:
             self.pending.copy_(torch.from_numpy(toks[:, 0].copy()))
             draft = torch.from_numpy(toks[:, 1:].copy()).to(self.dev)
             fl = torch.from_numpy(force).to(self.dev)
-            lg = self.sf_verify_step(k, draft)
-            self.sf_accept_commit(k, draft, lg, force_len=fl)
+            _, ids = self.sf_verify_step(k, draft, logits=False)
+            self.sf_accept_commit(k, draft, ids, force_len=fl)
             self.len_upper = int(done.max())
             if step < total - 1:
                 # pending of a finished block is the next prompt token, not the target's choice
@@ -397,30 +441,3 @@ class Engine:
             if k > 0 and self._D is not None:
                 self.sf_draft_step(k)
         return self.pending.clone()
-
-
-def random_device_weights(m, k, seed, two_stage=False):
-    """Random-init weights of model shape m (synth.ModelShape) generated directly on the GPU:
-    N(0, 0.02^2) matrices, norm gains 1 -- the recipe of the benchmark workloads.  Returns the two
-    dicts Engine.bind takes."""
-    g = torch.Generator(device="cuda")
-    g.manual_seed(seed)
-    dt = torch.bfloat16 if m.dtype == "bf16" else torch.float32
-
-    def rnd(*shape):
-        return (torch.randn(*shape, generator=g, device="cuda", dtype=torch.float32) * 0.02).to(dt)
-
-    def ones(*shape):
-        return torch.ones(*shape, device="cuda", dtype=dt)
-    d, hd, F, V, L = m.d_model, m.head_dim, m.d_ffn, m.vocab, m.n_layers
-    nqkv = (m.n_q_heads + 2 * m.n_kv_heads) * hd
-    tw = {"embed": rnd(V, d), "lm_head": rnd(V, d), "final_norm": ones(d),
-          "attn_norm": [ones(d) for _ in range(L)], "wqkv": [rnd(nqkv, d) for _ in range(L)],
-          "wo": [rnd(d, m.n_q_heads * hd) for _ in range(L)], "ffn_norm": [ones(d) for _ in range(L)],
-          "w_gate_up": [rnd(2 * F, d) for _ in range(L)], "w_down": [rnd(d, F) for _ in range(L)]}
-    dw = {"group_norm": ones(4, d), "w_ds": rnd(d, 4 * d), "pos_norm": ones(d), "w_pos": rnd(max(k, 1) * d, d),
-          "b_pos": rnd(max(k, 1) * d), "attn_norm": ones(d), "wqkv": rnd(nqkv, d), "wo": rnd(d, m.n_q_heads * hd),
-          "ffn_norm": ones(d), "w_gate_up": rnd(2 * F, d), "w_down": rnd(d, F), "out_norm": ones(d)}
-    if two_stage:      # the slot attention's own parameter set
-        dw.update({"sa_norm": ones(d), "sa_wqkv": rnd(nqkv, d), "sa_wo": rnd(d, m.n_q_heads * hd)})
-    return tw, dw

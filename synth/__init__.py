@@ -157,3 +157,54 @@ def random_qkv(seed, B, nq, Hq, Hkv, hd, cap, dtype, k_std=1.0):
 def kv_capacity(max_prefix, steps, k, align=64):
     need = int(max_prefix) + (steps + 1) * (k + 1)
     return (need + align - 1) // align * align
+
+
+def device_weights(m: ModelShape, k_max, seed, two_stage=False, std=0.02, device="cuda"):
+    """The same recipe drawn with torch's generator directly on `device` (for models too large to draw
+    on the host in reasonable time): N(0, std^2) matrices in the model dtype, norm gains 1.  Returns
+    (target dict, draft dict) of torch tensors in the layout the GPU engine binds: gate and up stacked as
+    w_gate_up = [gate; up].  host_weights() turns them into the oracle's numpy dicts."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed))
+    dt = torch.bfloat16 if m.dtype == "bf16" else torch.float32
+
+    def rnd(*shape):
+        return (torch.randn(*shape, generator=g, device=device, dtype=torch.float32) * std).to(dt)
+
+    def ones(*shape):
+        return torch.ones(*shape, device=device, dtype=dt)
+    d, hd, F, V, L = m.d_model, m.head_dim, m.d_ffn, m.vocab, m.n_layers
+    nqkv = (m.n_q_heads + 2 * m.n_kv_heads) * hd
+    tw = {"embed": rnd(V, d), "lm_head": rnd(V, d), "final_norm": ones(d),
+          "attn_norm": [ones(d) for _ in range(L)], "wqkv": [rnd(nqkv, d) for _ in range(L)],
+          "wo": [rnd(d, m.n_q_heads * hd) for _ in range(L)], "ffn_norm": [ones(d) for _ in range(L)],
+          "w_gate_up": [rnd(2 * F, d) for _ in range(L)], "w_down": [rnd(d, F) for _ in range(L)]}
+    dw = {"group_norm": ones(4, d), "w_ds": rnd(d, 4 * d), "pos_norm": ones(d), "w_pos": rnd(max(k_max, 1) * d, d),
+          "b_pos": rnd(max(k_max, 1) * d), "attn_norm": ones(d), "wqkv": rnd(nqkv, d), "wo": rnd(d, m.n_q_heads * hd),
+          "ffn_norm": ones(d), "w_gate_up": rnd(2 * F, d), "w_down": rnd(d, F), "out_norm": ones(d)}
+    if two_stage:      # the slot attention's own parameter set
+        dw.update({"sa_norm": ones(d), "sa_wqkv": rnd(nqkv, d), "sa_wo": rnd(d, m.n_q_heads * hd)})
+    return tw, dw
+
+
+def host_weights(tw, dw=None):
+    """device_weights() dicts -> float32 numpy dicts with the oracle's key names (w_gate / w_up apart)."""
+    def h(t):
+        return t.detach().float().cpu().numpy()
+
+    def conv(w, per_layer):
+        out = {}
+        for n, v in w.items():
+            if n == "w_gate_up":
+                halves = [h(x) for x in v] if per_layer else h(v)
+                if per_layer:
+                    out["w_gate"] = [np.ascontiguousarray(x[:x.shape[0] // 2]) for x in halves]
+                    out["w_up"] = [np.ascontiguousarray(x[x.shape[0] // 2:]) for x in halves]
+                else:
+                    out["w_gate"] = np.ascontiguousarray(halves[:halves.shape[0] // 2])
+                    out["w_up"] = np.ascontiguousarray(halves[halves.shape[0] // 2:])
+            else:
+                out[n] = [h(x) for x in v] if isinstance(v, list) else h(v)
+        return out
+    return conv(tw, True), (conv(dw, False) if dw is not None else None)

@@ -1,5 +1,6 @@
-"""The C-ABI library loads without a GPU, exports every symbol include/specformer.h declares, and
-its host-side argument checking returns the documented status codes.  No kernel is launched."""
+"""The C-ABI library loads without a GPU, exports every symbol include/specformer.h and
+include/specformer_aux.h declare, and its host-side argument checking returns the documented status
+codes.  No kernel is launched."""
 import ctypes as C
 import os
 import re
@@ -12,9 +13,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "specformer.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(sf_[a-z_0-9]+)\s*\(", text)))
+    names = set()
+    for header in ("specformer.h", "specformer_aux.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(sf_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported():
@@ -68,7 +72,7 @@ def test_steps_reject_bad_state_before_launching_anything():
     s = sfb.State()
     s.B, s.cap = 4, 128
     # not bound yet
-    assert L.sf_verify_step(ctx, C.byref(s), 4, None, 0, None, None) == sfb.SF_ESTATE
+    assert L.sf_verify_step(ctx, C.byref(s), 4, None, 0, None, None, None) == sfb.SF_ESTATE
     # bind with a missing pointer
     tw = sfb.TargetWeights()
     assert L.sf_bind(ctx, C.byref(tw), None) == sfb.SF_EINVAL
@@ -80,18 +84,25 @@ def test_steps_reject_bad_state_before_launching_anything():
     # draft step needs draft weights
     assert L.sf_draft_step(ctx, C.byref(s), 4, 1, 0, None, None, None) == sfb.SF_ESTATE
     # null state buffers
-    assert L.sf_verify_step(ctx, C.byref(s), 4, None, 0, None, None) == sfb.SF_EINVAL
+    assert L.sf_verify_step(ctx, C.byref(s), 4, None, 0, None, None, None) == sfb.SF_EINVAL
     for n in ("tk", "tv", "dk", "dv", "kv_len", "pending", "hooks", "n_new", "cu_new"):
         setattr(s, n, fake)
     s.workspace, s.workspace_bytes = 0x10000, 16
-    assert L.sf_verify_step(ctx, C.byref(s), 4, fake, 0, fake, None) == sfb.SF_ECAPACITY   # workspace
+    assert L.sf_verify_step(ctx, C.byref(s), 4, fake, 0, None, fake, None) == sfb.SF_ECAPACITY   # workspace
     s.workspace_bytes = L.sf_workspace_bytes(ctx, 4, 4, 128)
-    assert L.sf_verify_step(ctx, C.byref(s), 5, fake, 0, fake, None) == sfb.SF_EINVAL      # k > max_k
-    assert L.sf_verify_step(ctx, C.byref(s), 4, fake, 124, fake, None) == sfb.SF_ECAPACITY  # 124+5 > 128
-    assert L.sf_verify_step(ctx, C.byref(s), 4, None, 0, fake, None) == sfb.SF_EINVAL      # no draft tokens
+    assert L.sf_verify_step(ctx, C.byref(s), 5, fake, 0, None, fake, None) == sfb.SF_EINVAL      # k > max_k
+    assert L.sf_verify_step(ctx, C.byref(s), 4, fake, 124, None, fake, None) == sfb.SF_ECAPACITY  # 124+5 > 128
+    assert L.sf_verify_step(ctx, C.byref(s), 4, None, 0, None, fake, None) == sfb.SF_EINVAL      # no draft tokens
+    assert L.sf_verify_step(ctx, C.byref(s), 4, fake, 0, fake, None, None) == sfb.SF_EINVAL      # no target_ids
     s.workspace = 0x10010
-    assert L.sf_verify_step(ctx, C.byref(s), 4, fake, 0, fake, None) == sfb.SF_EINVAL      # misaligned
+    assert L.sf_verify_step(ctx, C.byref(s), 4, fake, 0, None, fake, None) == sfb.SF_EINVAL      # misaligned
+    s.workspace = 0x10000
     assert L.sf_accept_commit(ctx, C.byref(s), 4, fake, None, None, fake, fake, None) == sfb.SF_EINVAL
+    # call order: nothing was verified on this context, so there is no block to commit
+    assert L.sf_accept_commit(ctx, C.byref(s), 4, fake, fake, None, fake, fake, None) == sfb.SF_ESTATE
+    assert L.sf_op_accept(ctx, 4, 4, fake, None, None, fake, fake, fake, fake, fake, fake, None) == sfb.SF_EINVAL
+    assert L.sf_tune_linear(ctx, 99, 0) == sfb.SF_EINVAL and L.sf_tune_linear(ctx, 0, 0) == sfb.SF_OK
+    assert L.sf_tune_attention(ctx, 3) == sfb.SF_EINVAL and L.sf_tune_attention(None, 0) == sfb.SF_EINVAL
     # the slot attention's own weights come whole or not at all, and the two-stage wiring needs them
     s.workspace = 0x10000
     dw = sfb.DraftWeights()

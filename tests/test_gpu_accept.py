@@ -1,4 +1,5 @@
-"""sf_accept_commit against the oracle: bit-exact on identical logits, no guard band."""
+"""The acceptance rule (arg-max over stored logits + sf_op_accept, the launch behind sf_accept_commit) against
+the oracle: bit-exact on identical logits, no guard band."""
 import numpy as np
 import pytest
 import torch
@@ -41,7 +42,8 @@ def test_accept_commit_bit_exact(B, k, V, forced):
     eng.set_state(kv_len=len0, pending=pend0, n_new=np.zeros(B, np.int32))
     d = torch.from_numpy(draft).cuda()
     fl = torch.from_numpy(force).cuda() if forced else None
-    acc, out = eng.sf_accept_commit(k, d, torch.from_numpy(lg).cuda(), force_len=fl)
+    ids = eng.sf_op_argmax(torch.from_numpy(lg).cuda().reshape(B * (k + 1), V)).reshape(B, k + 1)
+    acc, out = eng.sf_op_accept(k, d, ids, force_len=fl)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(acc.cpu().numpy(), acc_o)
     np.testing.assert_array_equal(out.cpu().numpy(), out_o)

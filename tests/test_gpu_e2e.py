@@ -80,10 +80,10 @@ def test_tiny_fp32_whole_run(mode):
         draft = injected(ar, emitted, k, m.vocab, rng, 0.6) if step % 2 else d_o
         lg_o = orc.verify_step(k, draft)
         dg = torch.from_numpy(draft).cuda()
-        lg_g = eng.sf_verify_step(k, dg)
+        lg_g, ids_g = eng.sf_verify_step(k, dg)
         worst = max(worst, rel_err(to_np(lg_g), lg_o))
         acc_o, out_o = orc.accept_commit(k, draft, lg_o)
-        acc_g, out_g = eng.sf_accept_commit(k, dg, lg_g)
+        acc_g, out_g = eng.sf_accept_commit(k, dg, ids_g)
         np.testing.assert_array_equal(acc_g.cpu().numpy(), acc_o)
         np.testing.assert_array_equal(out_g.cpu().numpy(), out_o)
         np.testing.assert_array_equal(eng.kv_len.cpu().numpy(), orc.kv_len)
@@ -190,8 +190,9 @@ def test_bf16_slices_teacher_forced(name, mode):
         draft = injected(ar, emitted, k, m.vocab, rng, 0.7)
         lg_o = orc.verify_step(k, draft)
         dg = torch.from_numpy(draft).cuda()
-        lg_g = eng.sf_verify_step(k, dg)
+        lg_g, tid_g = eng.sf_verify_step(k, dg)
         lg_gn = to_np(lg_g)
+        np.testing.assert_array_equal(tid_g.cpu().numpy(), lg_gn.argmax(-1))   # the fused arg-max == arg-max of the stored logits
         err = np.abs(lg_gn - lg_o).max()
         assert rel_err(lg_gn, lg_o) < 2e-2
         ids_o, ids_g = lg_o.argmax(-1), lg_gn.argmax(-1)
@@ -209,7 +210,7 @@ def test_bf16_slices_teacher_forced(name, mode):
                 assert rel_err(got[b, :, :n], orc.tk[l][b, :, :n]) < 2e-2
         # acceptance on the GPU's own logits; exact where every compared row is outside the band
         acc_o, out_o = orc.accept_commit(k, draft, lg_o)
-        acc_g, out_g = eng.sf_accept_commit(k, dg, lg_g)
+        acc_g, out_g = eng.sf_accept_commit(k, dg, tid_g)
         rows_ok = safe.all(axis=1)
         np.testing.assert_array_equal(acc_g.cpu().numpy()[rows_ok], acc_o[rows_ok])
         np.testing.assert_array_equal(out_g.cpu().numpy()[rows_ok], out_o[rows_ok])
@@ -231,7 +232,7 @@ def test_bf16_verify_logits_against_unrounded_oracle():
     draft = np.random.default_rng(0).integers(0, m.vocab, (B, k)).astype(np.int32)
     eng.set_state(pending=ref.pending)
     lg_o = ref.verify_step(k, draft)
-    lg_g = to_np(eng.sf_verify_step(k, torch.from_numpy(draft).cuda()))
+    lg_g = to_np(eng.sf_verify_step(k, torch.from_numpy(draft).cuda())[0])
     assert rel_err(lg_g, lg_o) < 2e-2
 
 
@@ -242,8 +243,8 @@ def run_engine(eng, prompts, k, steps, draft_fn):
     for _ in range(steps):
         nat = eng.sf_draft_step(k) if k > 0 else None
         d = draft_fn(nat, outs)
-        lg = eng.sf_verify_step(k, d)
-        acc, out = eng.sf_accept_commit(k, d, lg)
+        _, ids = eng.sf_verify_step(k, d, logits=False)
+        acc, out = eng.sf_accept_commit(k, d, ids)
         acc, out = acc.cpu().numpy(), out.cpu().numpy()
         accs.append(acc)
         for b in range(eng.B):
@@ -300,16 +301,37 @@ def test_one_engine_switching_between_k0_and_k4():
     none = torch.zeros(B, 0, dtype=torch.int32, device="cuda")
     toks, rows = [eng.pending.clone()], []
     for _ in range(k + 1):
-        lg = eng.sf_verify_step(0, none)
+        lg, ids = eng.sf_verify_step(0, none)
         rows.append(lg[:, 0].clone())
-        _, out = eng.sf_accept_commit(0, none, lg)
+        _, out = eng.sf_accept_commit(0, none, ids)
         toks.append(out[:, 0].clone())
     for n, t in snap.items():
         getattr(eng, n).copy_(t)
     eng.len_upper = len0
     draft = torch.stack(toks[1:k + 1], 1).contiguous()
-    lg = eng.sf_verify_step(k, draft)
+    lg, ids = eng.sf_verify_step(k, draft)
     for i in range(k + 1):
         assert torch.equal(lg[:, i], rows[i]), i
-    acc, _ = eng.sf_accept_commit(k, draft, lg)
+    acc, _ = eng.sf_accept_commit(k, draft, ids)
     assert acc.cpu().tolist() == [k + 1] * B
+
+
+def test_accept_commit_wants_the_block_that_was_just_verified():
+    """Call order: one verified block is committed once, with the k it was verified with."""
+    m = synth.TINY
+    B, k, cap = 2, 3, 64
+    _, eng, _, _ = make_pair(m, B, cap, k, 3)
+    eng.prefill(synth.prompts([6, 9], m.vocab, 3))
+    draft = torch.zeros(B, k, dtype=torch.int32, device="cuda")
+    none = torch.zeros(B, 0, dtype=torch.int32, device="cuda")
+    _, ids = eng.sf_verify_step(k, draft)
+    with pytest.raises(sfb.SfError) as e:
+        eng.sf_accept_commit(0, none, ids[:, :1].contiguous())          # verified with k = 3, not 0
+    assert e.value.status == sfb.SF_ESTATE
+    len0 = eng.kv_len.clone()
+    acc, _ = eng.sf_accept_commit(k, draft, ids)
+    assert torch.equal(eng.kv_len, len0 + acc)
+    with pytest.raises(sfb.SfError) as e:
+        eng.sf_accept_commit(k, draft, ids)                              # nothing left to commit
+    assert e.value.status == sfb.SF_ESTATE
+    assert torch.equal(eng.kv_len, len0 + acc)                          # and nothing was enqueued

@@ -26,13 +26,14 @@ def test_graph_replay_equals_eager():
         return (torch.zeros(B, k, dtype=torch.int32, device="cuda"),
                 torch.zeros(B, k + 1, m.vocab, dtype=torch.float32, device="cuda"),
                 torch.zeros(B, dtype=torch.int32, device="cuda"),
+                torch.zeros(B, k + 1, dtype=torch.int32, device="cuda"),
                 torch.zeros(B, k + 1, dtype=torch.int32, device="cuda"))
 
     def step(eng, bufs):
-        d, lg, acc, out = bufs
+        d, lg, acc, out, ids = bufs
         eng.sf_draft_step(k, draft_out=d)
-        eng.sf_verify_step(k, d, logits_out=lg)
-        eng.sf_accept_commit(k, d, lg, accept_out=acc, tokens_out=out)
+        eng.sf_verify_step(k, d, logits_out=lg, ids_out=ids)
+        eng.sf_accept_commit(k, d, ids, accept_out=acc, tokens_out=out)
 
     gb, eb = buffers(), buffers()
     graph.pin_len_upper()                      # grids depend only on this host-side bound
@@ -54,7 +55,7 @@ def test_graph_replay_equals_eager():
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
-        for a, b, name in zip(gb, eb, ("draft", "logits", "accept_len", "out_tokens")):
+        for a, b, name in zip(gb, eb, ("draft", "logits", "accept_len", "out_tokens", "target_ids")):
             assert torch.equal(a, b), (it, name)
         for name in ("kv_len", "pending", "n_new", "cu_new", "hooks"):
             assert torch.equal(getattr(graph, name), getattr(eager, name)), (it, name)

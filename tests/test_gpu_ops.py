@@ -110,7 +110,7 @@ def test_linear_bf16_every_tile_and_split_gives_the_same_bits(M, N, K):
         for split in (1, 2, 4):
             first = None
             for tile in range(1, L.sf_linear_num_tiles() + 1):
-                sfb.check(L.sf_tune_linear(tile, split), "sf_tune_linear")
+                eng.sf_tune_linear(tile, split)
                 y = eng.sf_op_linear(xd, None, out_f32=True, packed=(packed, N))
                 few = eng.sf_op_linear(xd[:7].contiguous(), None, out_f32=True, packed=(packed, N))
                 torch.cuda.synchronize()
@@ -120,7 +120,7 @@ def test_linear_bf16_every_tile_and_split_gives_the_same_bits(M, N, K):
                 assert torch.equal(y, first), (tile, split)
                 assert torch.equal(few, first[:7]), (tile, split)
     finally:
-        L.sf_tune_linear(0, 0)
+        eng.sf_tune_linear(0, 0)
 
 
 @pytest.mark.parametrize("M,N,K", [(160, 392, 2048), (77, 264, 200), (333, 520, 1792), (5, 128, 4096)])
@@ -148,7 +148,7 @@ def test_rmsnorm_linear_fused(M, N, K):
         for split in (1, 2, 4):
             first = None
             for tile in range(1, L.sf_linear_num_tiles() + 1):
-                sfb.check(L.sf_tune_linear(tile, split), "sf_tune_linear")
+                eng.sf_tune_linear(tile, split)
                 y = eng.sf_op_rmsnorm_linear(xd, gd, None, out_f32=True, packed=(packed, N))
                 few = eng.sf_op_rmsnorm_linear(xd[:3].contiguous(), gd, None, out_f32=True, packed=(packed, N))
                 torch.cuda.synchronize()
@@ -158,7 +158,7 @@ def test_rmsnorm_linear_fused(M, N, K):
                 assert torch.equal(y, first), (tile, split)
                 assert torch.equal(few, first[:3]), (tile, split)
     finally:
-        L.sf_tune_linear(0, 0)
+        eng.sf_tune_linear(0, 0)
 
 
 @pytest.mark.parametrize("M,N,K", [(20, 768, 256), (77, 264, 200), (130, 1024, 1024)])
@@ -261,6 +261,52 @@ def test_argmax_bit_exact(V):
     np.testing.assert_array_equal(ids, want)
 
 
+def integer_operands(M, N, K, seed):
+    """Small-integer rows and weights: every product and partial sum is exact in fp32, so the GPU's
+    accumulators equal the oracle's logits bit for bit and equal values (ties) abound."""
+    g = synth.rng(seed, N)
+    x = g.integers(-2, 3, (M, K)).astype(np.float32)
+    w = g.integers(-3, 4, (N, K)).astype(np.float32)
+    return x, w
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("M,V", [(5, 32000), (160, 32000), (37, 128256), (200, 152064), (23, 1000), (3, 136)])
+def test_lm_head_fused_argmax_bit_exact(dtype, M, V):
+    """The LM head with its arg-max (bf16: per-column-tile partials from the linear kernel's epilogue, logits
+    optional) against the oracle's linear + arg-max: planted ties inside a lane group, across the waves of a
+    workgroup and across column-tile edges, plus the ties the integer operands produce by themselves."""
+    if dtype == "f32" and M * V > 4e6:
+        pytest.skip("fp32 mode serves the small configuration only")
+    K = 64
+    x, w = integer_operands(M, V, K, 21)
+    top = np.full(K, 3.0, np.float32)
+    for r, (c0, c1) in enumerate([(5, 17), (31, 32), (127, 128), (255, 256), (100, V - 1), (V - 2, V - 1)][:M]):
+        x[r] = 2.0                                    # row r: columns c0 and c1 both reach the largest possible logit
+        w[c0] = top; w[c1] = top
+    if M > 8:
+        x[8, 3] = np.nan                              # a row of NaN logits: nothing comparable -> 0
+    ref = sfo.linear(x, w)
+    want = np.array([sfo.argmax(ref[r]) for r in range(M)], np.int32)
+    eng = engine_only(shape_for(dtype, 2, 2, 64), 1, 64, 1)
+    xd, wd = dev(x, dtype), dev(w, dtype)
+    ids = eng.sf_op_linear_argmax(xd, wd).cpu().numpy()
+    np.testing.assert_array_equal(ids, want)
+    ids2, lg = eng.sf_op_linear_argmax(xd, wd, want_logits=True)
+    np.testing.assert_array_equal(ids2.cpu().numpy(), want)
+    finite = ~np.isnan(ref)
+    np.testing.assert_array_equal(to_np(lg)[finite], ref[finite])
+    if dtype == "bf16" and M == 160:                  # every tile shape leaves the same answer
+        packed = eng.sf_pack_weight(wd)
+        try:
+            for tile in range(1, sfb.lib().sf_linear_num_tiles() + 1):
+                eng.sf_tune_linear(tile, 0)
+                got = eng.sf_op_linear_argmax(xd, None, packed=(packed, V)).cpu().numpy()
+                np.testing.assert_array_equal(got, want, err_msg=f"tile {tile}")
+        finally:
+            eng.sf_tune_linear(0, 0)
+
+
 @pytest.mark.parametrize("mode", [sfb.SF_MASK_CAUSAL, sfb.SF_MASK_BIDIR])
 @pytest.mark.parametrize("Hq,Hkv,hd,nq,chunk", [(8, 2, 64, 5, 0), (8, 2, 128, 5, 0), (16, 2, 128, 5, 0),
                                                  (8, 2, 64, 5, 16), (8, 2, 128, 7, 16), (4, 4, 128, 1, 0)])
@@ -291,23 +337,21 @@ def test_rope_attention_fused(mode, Hq, Hkv, hd, nq, chunk):
     ref = sfo.attention(q_ref.reshape(B, nq, Hq, hd), kc_ref, vc_ref, lens, mode)
 
     kvl = torch.from_numpy(lens).cuda()
-    L = sfb.lib()
-    L.sf_tune_attention(chunk)
-    try:
+    if True:
         eng = engine_only(shape_for("bf16", Hq, Hkv, hd), B, cap, max(nq - 1, 1))
+        eng.sf_tune_attention(chunk)
         eng.sf_kv_import(kc, "dk"); eng.sf_kv_import(vc, "dv")
         out = eng.sf_op_rope_attention(dev(qkv, "bf16"), kvl, nq, eng.dk, eng.dv, mode)
         torch.cuda.synchronize()
         got, kg, vg = to_np(out), to_np(eng.sf_kv_export("dk")), to_np(eng.sf_kv_export("dv"))
         # the two-kernel route on a second pair of caches
         eng2 = engine_only(shape_for("bf16", Hq, Hkv, hd), B, cap, max(nq - 1, 1))
+        eng2.sf_tune_attention(chunk)
         eng2.sf_kv_import(kc, "dk"); eng2.sf_kv_import(vc, "dv")
         q_rot = eng2.sf_op_rope_kv_append(dev(qkv, "bf16"), kvl, nq, eng2.dk, eng2.dv)
         out2 = eng2.sf_op_attention(q_rot.view(B, nq, Hq, hd), eng2.dk, eng2.dv, kvl, nq, mode)
         torch.cuda.synchronize()
         got2, kg2, vg2 = to_np(out2), to_np(eng2.sf_kv_export("dk")), to_np(eng2.sf_kv_export("dv"))
-    finally:
-        L.sf_tune_attention(0)
     assert np.all(np.isfinite(got))
     assert rel_err(got, ref) < BF16_TOL
     live = np.zeros((B, cap), bool)

@@ -146,14 +146,14 @@ def test_norm_linear_exact_mode_is_norm_then_linear():
 
 def test_norm_linear_bf16_mode_rounding_points():
     """round_bf16 mode: the gains are folded into the weight (w*g rounded to bf16 once), the product
-    runs on the bf16 copy of the raw row, the row factor comes from the unrounded row and is applied
+    runs on the bf16 copy of the raw row, the row factor comes from that same copy and is applied
     unrounded.  Pinned against a numpy composition with torch's bf16 cast."""
     rs = np.random.default_rng(4)
     M, K, N = 6, 40, 9
     x = rs.standard_normal((M, K)) * 3.0                       # fp32-like values, not bf16-representable
     w = _bf16(rs.standard_normal((N, K)) * 0.05).astype(np.float32)
     for g in (np.ones(K, np.float32), _bf16(rs.uniform(0.25, 2.0, K)).astype(np.float32)):
-        rinv = 1.0 / np.sqrt((x * x).mean(-1, keepdims=True) + 1e-6)
+        rinv = 1.0 / np.sqrt((_bf16(x) ** 2).mean(-1, keepdims=True) + 1e-6)
         want = (_bf16(x) @ _bf16(w.astype(np.float64) * g).T) * rinv
         got = sfo.norm_linear(x, g, w, round_bf16=True)
         np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
@@ -164,8 +164,9 @@ def test_norm_linear_bf16_mode_rounding_points():
 
 
 def test_norm_linear_bf16_mode_stays_within_the_rounding_bound_of_exact():
-    """Each product x_k * (w g)_k is perturbed by two bf16 roundings (unit roundoff u = 2^-8), so
-    |y_rb - y_exact| <= ((1+u)^2 - 1) * rinv * sum_k |x_k w_k g_k|, element by element."""
+    """Each product x_k * (w g)_k is perturbed by two bf16 roundings (unit roundoff u = 2^-8) and the
+    row factor, a function of sum x_k^2 with every term within (1 +- u)^2, by at most a factor
+    (1 + u), so |y_rb - y_exact| <= ((1+u)^3 - 1) * rinv * sum_k |x_k w_k g_k|, element by element."""
     rs = np.random.default_rng(5)
     M, K, N = 8, 96, 12
     x = rs.standard_normal((M, K)) * 0.7
@@ -175,6 +176,6 @@ def test_norm_linear_bf16_mode_stays_within_the_rounding_bound_of_exact():
     got = sfo.norm_linear(x, g, w, round_bf16=True)
     u = 2.0 ** -8
     rinv = 1.0 / np.sqrt((x * x).mean(-1, keepdims=True) + 1e-6)
-    bound = ((1 + u) ** 2 - 1) * (np.abs(x) @ np.abs(w.astype(np.float64) * g).T) * rinv
+    bound = ((1 + u) ** 3 - 1) * (np.abs(x) @ np.abs(w.astype(np.float64) * g).T) * rinv
     assert np.all(np.abs(got - exact) <= bound * (1 + 1e-9))
     assert np.abs(got - exact).max() > 0                       # and the rounding really happens
