@@ -288,6 +288,16 @@ size_t sf_argmax_workspace_bytes(int32_t M);
 sf_status sf_op_argmax(const sf_ctx *ctx, const float *logits, int32_t M, int32_t V, int32_t *ids,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* sf_op_argmax for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the workspace, same
+ * result.  The partials live in a static device array of the library (512 KiB, held on every GPU the library
+ * runs on until the process ends), sized for M <= SF_ARGMAX_NOALLOC_MAX_ROWS rows: SF_ECAPACITY beyond that.
+ * The call allocates nothing and frees nothing.  All calls on one GPU share that array: calls that overlap
+ * in time on one GPU (different streams, or different threads) race -- serialise them. */
+#define SF_ARGMAX_NOALLOC_MAX_ROWS 4096
+sf_status sf_op_argmax_noalloc(const sf_ctx *ctx, const float *logits, int32_t M, int32_t V, int32_t *ids,
+                               void *stream);
+
 /* The acceptance rule alone, on explicit state arrays (what sf_accept_commit launches after its call-order
  * check): all pointers dev; kv_len, pending: [B] in/out; n_new: [B] out; cu_new: [B+1] out. */
 sf_status sf_op_accept(const sf_ctx *ctx, int32_t B, int32_t k, const int32_t *draft_tokens,

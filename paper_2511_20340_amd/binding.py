@@ -18,7 +18,7 @@ EXPORTS = [
     "sf_op_attention", "sf_packed_weight_bytes", "sf_pack_weight", "sf_linear_workspace_bytes", "sf_op_linear",
     "sf_op_rmsnorm_linear", "sf_op_linear_swiglu", "sf_linear_argmax_workspace_bytes", "sf_op_linear_argmax",
     "sf_op_rmsnorm", "sf_op_rope_kv_append", "sf_rope_attention_workspace_bytes", "sf_op_rope_attention",
-    "sf_op_silu_mul", "sf_argmax_workspace_bytes", "sf_op_argmax", "sf_op_accept", "sf_strerror",
+    "sf_op_silu_mul", "sf_argmax_workspace_bytes", "sf_op_argmax", "sf_op_argmax_noalloc", "sf_op_accept", "sf_strerror",
     "sf_last_hip_error", "sf_version",
     # include/specformer_aux.h
     "sf_tune_linear", "sf_linear_num_tiles", "sf_linear_config", "sf_tune_attention", "sf_calib_copy",
@@ -114,6 +114,7 @@ def lib():
     L.sf_argmax_workspace_bytes.argtypes = [i32]
     L.sf_argmax_workspace_bytes.restype = sz
     L.sf_op_argmax.argtypes = [vp, vp, i32, i32, vp, vp, sz, vp]
+    L.sf_op_argmax_noalloc.argtypes = [vp, vp, i32, i32, vp, vp]
     L.sf_calib_copy.argtypes = [vp, vp, sz, vp]
     L.sf_profile_begin.argtypes = [vp]
     L.sf_profile_end.argtypes = [vp, P(C.c_double), P(i32), i32]

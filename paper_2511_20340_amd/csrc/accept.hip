@@ -9,6 +9,13 @@
 // Ties resolve to the lowest index; NaN never wins; a row without any comparable value gives 0.
 #include "sf_internal.h"
 #include <limits.h>
+#include <mutex>
+
+// Scratch of the entry point that must not allocate (sf_op_argmax_noalloc): the arg-max partials of up to
+// ARGMAX_NOALLOC_MAX_ROWS logits rows, [rows][ARGMAX_SEGS] values followed by [rows][ARGMAX_SEGS] indices.
+// Every GPU the library runs on holds its own copy of this array until the process ends; host code reaches
+// it only through the per-device address that hipGetSymbolAddress returns.
+static __device__ __align__(256) unsigned char scratch[(size_t)sf::ARGMAX_NOALLOC_MAX_ROWS * sf::ARGMAX_SEGS * 8];
 
 namespace sf {
 namespace {
@@ -132,6 +139,35 @@ hipError_t launch_argmax_partial(const float *logits, int M, int V, float *pmax,
 hipError_t launch_argmax_final(const float *pmax, const int32_t *pidx, int M, int n_part, int stride, int32_t *ids,
                                hipStream_t s) {
   argmax_final_kernel<<<(M + 3) / 4, 256, 0, s>>>(pmax, pidx, M, n_part, stride, ids);
+  return hipGetLastError();
+}
+
+hipError_t launch_argmax_noalloc(const float *logits, int M, int V, int32_t *ids, hipStream_t s) {
+  constexpr int MAX_DEVICES = 64;
+  static void *dev_scratch[MAX_DEVICES];  // the array's address on each device, resolved once
+  static std::mutex mu;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  void *p;
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!dev_scratch[dev]) {
+      void *sym = nullptr;
+      e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+      if (e != hipSuccess) return e;
+      dev_scratch[dev] = sym;
+    }
+    p = dev_scratch[dev];
+  }
+  float *pmax = reinterpret_cast<float *>(p);
+  int32_t *pidx = reinterpret_cast<int32_t *>(static_cast<char *>(p) + (size_t)ARGMAX_NOALLOC_MAX_ROWS * ARGMAX_SEGS * 4);
+  // every partial the finish reads is written by the first pass of the same call: nothing to clear
+  argmax_partial_kernel<<<dim3(ARGMAX_SEGS, M), 256, 0, s>>>(logits, V, pmax, pidx);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  argmax_final_kernel<<<(M + 3) / 4, 256, 0, s>>>(pmax, pidx, M, ARGMAX_SEGS, ARGMAX_SEGS, ids);
   return hipGetLastError();
 }
 

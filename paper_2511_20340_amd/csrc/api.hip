@@ -778,6 +778,15 @@ sf_status sf_op_argmax(const sf_ctx *c, const float *logits, int32_t M, int32_t 
   return r.st;
 }
 
+sf_status sf_op_argmax_noalloc(const sf_ctx *c, const float *logits, int32_t M, int32_t V, int32_t *ids, void *stream) {
+  if (!c || !logits || !ids || M < 1 || V < 1) return SF_EINVAL;
+  if (M > ARGMAX_NOALLOC_MAX_ROWS) return SF_ECAPACITY;
+  (void)hipGetLastError();
+  const hipError_t e = launch_argmax_noalloc(logits, M, V, ids, (hipStream_t)stream);
+  if (e != hipSuccess) { c->hip_err = (int)e; return SF_EHIP; }
+  return SF_OK;
+}
+
 sf_status sf_calib_copy(void *dst, const void *src, size_t bytes, void *stream) {
   if (!dst || !src || bytes % 16 || (((uintptr_t)dst | (uintptr_t)src) % 16)) return SF_EINVAL;
   return launch_calib_copy(src, dst, bytes, (hipStream_t)stream) == hipSuccess ? SF_OK : SF_EHIP;

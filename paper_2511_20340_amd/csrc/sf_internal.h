@@ -188,6 +188,9 @@ hipError_t launch_kv_convert(const void *src, void *dst, int is_v, int to_tiled,
                              int dtype, hipStream_t s);
 
 constexpr int ARGMAX_SEGS = 16;
+constexpr int ARGMAX_NOALLOC_MAX_ROWS = 4096;  // rows the allocation-free arg-max entry point accepts
+// arg-max over stored logits with its partials in a static device array (no workspace argument)
+hipError_t launch_argmax_noalloc(const float *logits, int M, int V, int32_t *ids, hipStream_t s);
 hipError_t launch_argmax_partial(const float *logits, int M, int V, float *pmax, int32_t *pidx, hipStream_t s);
 // ids[row] = column of the best of the row's n_part partials pmax/pidx[row * stride + 0..n_part)
 hipError_t launch_argmax_final(const float *pmax, const int32_t *pidx, int M, int n_part, int stride, int32_t *ids,

@@ -401,6 +401,13 @@ class Engine:
         self._keep_ws = ws
         return ids
 
+    def sf_op_argmax_noalloc(self, logits, ids):
+        """ids (preallocated int32 [M]) = row arg-max of logits; nothing is allocated on the way."""
+        M, V = logits.shape
+        sfb.check(self.lib.sf_op_argmax_noalloc(self.ctx, _ptr(logits), M, V, _ptr(ids), _stream()),
+                  "sf_op_argmax_noalloc", self.ctx)
+        return ids
+
     # ---- prefill: chunked verify with forced acceptance --------------------------------------
     def prefill(self, prompts):
         """Feeds every prompt through sf_verify_step in blocks of max_k+1 tokens with forced
