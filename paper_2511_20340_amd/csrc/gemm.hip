@@ -83,9 +83,12 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const Epilogu
   const int ln = lane & 31, lh = lane >> 5;
   if (split_k > 1) {
     // Partial tiles in register order: [tile][split][wave][TM][TN][reg][lane], written and read with
-    // agent-scope accesses.  Hand-over: every wave releases its stores at agent scope, the workgroup
-    // meets at a barrier, one thread takes the tile's ticket (acquire-release, agent scope); the
-    // workgroup that draws the last ticket acquires at agent scope before it reads the other splits.
+    // agent-scope atomic accesses only (write-through stores, loads that bypass the caches), so no
+    // cache-wide write-back or invalidate is needed for them.  Hand-over: every wave waits until its
+    // stores are acknowledged and releases at workgroup scope, the workgroup meets at a barrier, and one
+    // thread takes the tile's ticket with an acquire-release read-modify-write at agent scope; that
+    // chain (workgroup release -> barrier -> agent acq_rel ticket ... agent acq_rel ticket -> barrier)
+    // orders every split's stores before the loads of the workgroup that draws the last ticket.
     const size_t tile = (size_t)tn * tiles_m + tm;
     constexpr size_t PER_WAVE = (size_t)TM * TN * 64 * 16;
     float *mine = partial + ((tile * split_k + ks) * NW + wave) * PER_WAVE;
@@ -100,12 +103,12 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const Epilogu
     if (sS && tid < BM)
       __hip_atomic_store(ssq_part + (tile * split_k + ks) * BM + tid, sS[tid], __ATOMIC_RELAXED,
                          __HIP_MEMORY_SCOPE_AGENT);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __builtin_amdgcn_s_waitcnt(0);  // all counters: this wave's write-through stores have been acknowledged
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     if (tid == 0) s_ticket = __hip_atomic_fetch_add(&tickets[tile], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (s_ticket != (unsigned)(split_k - 1)) return;  // not the last split of this tile
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 #pragma unroll
     for (int a = 0; a < TM; ++a)
 #pragma unroll
