@@ -193,6 +193,8 @@ def main():
     ap.add_argument("--seeded-state", action="store_true",
                     help="skip prefill and the plain-greedy reference run: seed caches, hooks and pending tokens "
                          "directly (values do not change the work); only the natural-draft pass runs. For profilers.")
+    ap.add_argument("--prefill-block", type=int, default=64,
+                    help="prompt tokens per sequence and sf_verify_step call during the chunked prefill")
     ap.add_argument("--no-graph", dest="graph", action="store_false",
                     help="launch every kernel eagerly instead of replaying one HIP graph per step")
     args = ap.parse_args()
@@ -249,7 +251,7 @@ def main():
         eng.set_state(kv_len=lens, pending=synth.rng(wl.seed, 5).integers(0, m.vocab, B).astype(np.int32),
                       n_new=np.ones(B, np.int32))
     else:
-        eng.prefill(prompts)
+        eng.prefill(prompts, block=max(args.prefill_block, k + 1))
     torch.cuda.synchronize()
     t_prefill = time.time() - t0
     snap = {n: getattr(eng, n).clone() for n in ("kv_len", "pending", "n_new", "cu_new", "hooks")}
@@ -430,7 +432,8 @@ def main():
                    "q_heads": m.n_q_heads, "kv_heads": m.n_kv_heads, "head_dim": m.head_dim, "d_ffn": m.d_ffn,
                    "vocab": m.vocab, "draft_wiring": args.draft_wiring, "draft_mask": args.draft_mask, "drafts": "natural (the random-init draft block's own tokens)",
                    "state": "seeded caches (no prefill)" if args.seeded_state else
-                            "real chunked prefill through sf_verify_step", "prefill_s": round(t_prefill, 3),
+                            f"real chunked prefill through sf_verify_step, blocks of {max(args.prefill_block, k + 1)} "
+                            "prompt tokens", "prefill_s": round(t_prefill, 3),
                    "launch": "one HIP graph replay per step" if args.graph else "eager launches"},
         "kappa": tok_nat / (steps * B),
         "step_us": 1e6 * dt_nat / steps,

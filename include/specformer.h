@@ -126,7 +126,8 @@ typedef struct {
   size_t workspace_bytes;
 } sf_state;
 
-/* Context.  host.  max_B <= 4096, 0 <= max_k <= 15.  target and draft must agree on every field
+/* Context.  host.  max_B <= 4096, 0 <= max_k <= 127 (decoding uses a handful of slots; blocks of up to 128
+ * rows serve chunked prefill: sf_verify_step over prompt tokens + sf_accept_commit with force_len).  target and draft must agree on every field
  * but n_layers (draft: 1).  SF_EUNSUPPORTED unless head_dim in {64,128} for SF_BF16 (any multiple
  * of 8 up to 256 for SF_F32), d_model % 8 == 0, d_ffn % 32 == 0, (n_q_heads * head_dim) % 32 == 0. */
 sf_status sf_create(const sf_model_cfg *target, const sf_model_cfg *draft, int32_t max_B, int32_t max_k,
@@ -198,7 +199,7 @@ sf_status sf_kv_export(const sf_ctx *ctx, const void *tiled, void *plain, int32_
 /* Hybrid-mask ragged attention (SpecFormer: MSA over the cached context + SA over the block).
  * q, out: dev elem [B][n_q][Hq][hd]; kc, vc: one layer's tiled caches with the block's own K/V
  * already stored at positions [kv_len[b], kv_len[b]+n_q); softmax(q.k/sqrt(hd)) in fp32.
- * Requires (Hq/Hkv)*n_q <= 64 for SF_BF16.  workspace as in sf_state (split-KV partials);
+ * Requires (Hq/Hkv)*n_q <= 1024 for SF_BF16 (row tiles of 32 rows; every row tile streams the keys once).  workspace as in sf_state (split-KV partials);
  * sf_attention_workspace_bytes gives its size. */
 size_t sf_attention_workspace_bytes(const sf_ctx *ctx, int32_t B, int32_t n_q, int32_t host_len_upper);
 sf_status sf_op_attention(const sf_ctx *ctx, const void *q, const void *kc, const void *vc,

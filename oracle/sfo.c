@@ -394,7 +394,6 @@ int sfo_draft_step(const sfo_cfg *c, const sfo_draft_weights *w, const float *lm
 int sfo_accept_commit(sfo_state *s, int k, int V, const int32_t *draft, const double *logits,
                       const int32_t *force_len, int32_t *accept_len, int32_t *out_tokens) {
   int B = s->B, nq = k + 1;
-  if (nq > 64) return -1;
   if (force_len)
     for (int b = 0; b < B; ++b)
       if (force_len[b] < 0 || force_len[b] > nq) return -1;

@@ -118,7 +118,7 @@ bool same_shape(const sf_model_cfg &a, const sf_model_cfg &b) {
 sf_status check_attn_shape(const sf_model_cfg &m, int n_q) {
   const int G = m.n_q_heads / m.n_kv_heads;
   if (m.dtype == SF_BF16) {
-    if (G * n_q > 64) return SF_EUNSUPPORTED;
+    if (G * n_q > 1024) return SF_EUNSUPPORTED;  // 32 row tiles of 32 rows per (sequence, kv head)
   } else {
     if (n_q * m.head_dim > 2048) return SF_EUNSUPPORTED;
   }
@@ -287,7 +287,7 @@ extern "C" {
 
 sf_status sf_create(const sf_model_cfg *t, const sf_model_cfg *d, int32_t max_B, int32_t max_k, sf_ctx **out) {
   if (!t || !d || !out) return SF_EINVAL;
-  if (max_B < 1 || max_B > 4096 || max_k < 0 || max_k > 15) return SF_EINVAL;
+  if (max_B < 1 || max_B > 4096 || max_k < 0 || max_k > 127) return SF_EINVAL;
   if (t->n_layers < 1 || d->n_layers != 1 || !same_shape(*t, *d)) return SF_EINVAL;
   if (t->d_model < 8 || t->n_q_heads < 1 || t->n_kv_heads < 1 || t->head_dim < 8 || t->d_ffn < 8 || t->vocab < 1)
     return SF_EINVAL;
@@ -534,7 +534,7 @@ sf_status sf_accept_commit(sf_ctx *c, const sf_state *st, int32_t k, const int32
 sf_status sf_op_accept(const sf_ctx *c, int32_t B, int32_t k, const int32_t *draft, const int32_t *target_ids,
                        const int32_t *force_len, int32_t *accept_len, int32_t *out_tokens, int32_t *kv_len,
                        int32_t *pending, int32_t *n_new, int32_t *cu_new, void *stream) {
-  if (!c || B < 1 || k < 0 || k > 15) return SF_EINVAL;
+  if (!c || B < 1 || k < 0 || k > 127) return SF_EINVAL;
   if (!target_ids || !accept_len || !out_tokens || !kv_len || !pending || !n_new || !cu_new) return SF_EINVAL;
   if (k > 0 && !draft && !force_len) return SF_EINVAL;
   Run r{c, (hipStream_t)stream};

@@ -155,12 +155,13 @@ class Engine:
         self._T, self._D = T, D
         sfb.check(self.lib.sf_bind(self.ctx, C.byref(T), C.byref(D) if D is not None else None), "sf_bind")
 
-    def bind_shared(self, other):
-        """Bind the target weights that another engine has already uploaded and packed (no copy,
-        no draft block): for a plain-decoding engine next to a speculative one."""
-        self.w, self._T, self._D = other.w, other._T, None
+    def bind_shared(self, other, with_draft=False):
+        """Bind the weights that another engine has already uploaded and packed (no copy): the target's
+        only (a plain-decoding engine next to a speculative one), or the draft block's too."""
+        self.w, self._T, self._D = other.w, other._T, (other._D if with_draft else None)
         self._keep = other._keep
-        sfb.check(self.lib.sf_bind(self.ctx, C.byref(self._T), None), "sf_bind")
+        sfb.check(self.lib.sf_bind(self.ctx, C.byref(self._T), C.byref(self._D) if self._D is not None else None),
+                  "sf_bind")
 
     # ---- the three steps ---------------------------------------------------------------------
     def sf_draft_step(self, k, mask=sfb.SF_MASK_BIDIR, draft_out=None, logits_out=None):
@@ -409,42 +410,65 @@ class Engine:
         return ids
 
     # ---- prefill: chunked verify with forced acceptance --------------------------------------
-    def prefill(self, prompts):
-        """Feeds every prompt through sf_verify_step in blocks of max_k+1 tokens with forced
-        commits, right-aligned so that all sequences finish with the last block, and runs
-        sf_draft_step after every block so the draft cache follows.  Returns the first emitted
-        token of every sequence (device tensor)."""
-        k, q = self.max_k, self.max_k + 1
-        lens = np.array([len(p) for p in prompts], np.int64)
-        nblk = (lens + q - 1) // q
-        total = int(nblk.max())
-        self.set_state(kv_len=np.zeros(self.B, np.int32), pending=np.zeros(self.B, np.int32),
-                       n_new=np.zeros(self.B, np.int32))
-        done = np.zeros(self.B, np.int64)
-        for step in range(total):
-            toks = np.zeros((self.B, q), np.int32)
-            force = np.zeros(self.B, np.int32)
-            nxt = np.zeros(self.B, np.int32)
-            for b, p in enumerate(prompts):
-                if step < total - nblk[b]:
-                    continue                      # this sequence starts later
-                first = lens[b] - (nblk[b] - 1) * q if done[b] == 0 else q   # short block first
-                seg = p[done[b]:done[b] + first]
-                toks[b, :len(seg)] = seg
-                force[b] = len(seg)
-                done[b] += len(seg)
-                nxt[b] = p[done[b]] if done[b] < lens[b] else -1
-            self.pending.copy_(torch.from_numpy(toks[:, 0].copy()))
-            draft = torch.from_numpy(toks[:, 1:].copy()).to(self.dev)
-            fl = torch.from_numpy(force).to(self.dev)
-            _, ids = self.sf_verify_step(k, draft, logits=False)
-            self.sf_accept_commit(k, draft, ids, force_len=fl)
-            self.len_upper = int(done.max())
-            if step < total - 1:
-                # pending of a finished block is the next prompt token, not the target's choice
-                pend = self.pending.cpu().numpy()
-                pend[nxt >= 0] = nxt[nxt >= 0]
-                self.pending.copy_(torch.from_numpy(pend))
-            if k > 0 and self._D is not None:
-                self.sf_draft_step(k)
-        return self.pending.clone()
+    def prefill(self, prompts, block=None):
+        """Feeds every prompt through sf_verify_step in blocks of `block` tokens (default max_k+1) with forced
+        commits, right-aligned so that all sequences finish with the last block, and runs sf_draft_step after
+        every block so the draft cache follows.  A block longer than max_k+1 runs on a helper engine created
+        for that block length (same weights, same caches); its final lengths, pending tokens and newest hooked
+        rows are then handed to this engine.  Returns the first emitted token of every sequence (device)."""
+        q = self.max_k + 1 if block is None else int(block)
+        if q <= self.max_k + 1:
+            return _prefill_blocks(self, prompts, q, self.max_k)
+        helper = Engine(self.cfg, self.B, self.cap, q - 1, device=self.dev, share_caches=self)
+        helper.bind_shared(self, with_draft=self._D is not None)
+        first = _prefill_blocks(helper, prompts, q, max(self.max_k, 1))
+        # hand-over: committed lengths, pending tokens, and every sequence's newest committed row of hooks
+        self.kv_len.copy_(helper.kv_len)
+        self.pending.copy_(helper.pending)
+        last = (helper.n_new.to(torch.int64) - 1).clamp_(min=0)
+        rows = helper.hooks[torch.arange(self.B, device=self.dev), last]          # [B, 4, d]
+        self.hooks.zero_()
+        self.hooks[:, 0] = rows
+        self.n_new.copy_((helper.n_new > 0).to(torch.int32))
+        self.len_upper = helper.len_upper
+        torch.cuda.current_stream().synchronize()
+        helper.close()
+        return first
+
+
+def _prefill_blocks(eng, prompts, q, k_draft):
+    """Chunked prefill on `eng` in blocks of q <= eng.max_k + 1 prompt tokens (see Engine.prefill)."""
+    k = q - 1
+    lens = np.array([len(p) for p in prompts], np.int64)
+    nblk = (lens + q - 1) // q
+    total = int(nblk.max())
+    eng.set_state(kv_len=np.zeros(eng.B, np.int32), pending=np.zeros(eng.B, np.int32),
+                  n_new=np.zeros(eng.B, np.int32))
+    done = np.zeros(eng.B, np.int64)
+    for step in range(total):
+        toks = np.zeros((eng.B, q), np.int32)
+        force = np.zeros(eng.B, np.int32)
+        nxt = np.zeros(eng.B, np.int32)
+        for b, p in enumerate(prompts):
+            if step < total - nblk[b]:
+                continue                      # this sequence starts later
+            first = lens[b] - (nblk[b] - 1) * q if done[b] == 0 else q   # short block first
+            seg = p[done[b]:done[b] + first]
+            toks[b, :len(seg)] = seg
+            force[b] = len(seg)
+            done[b] += len(seg)
+            nxt[b] = p[done[b]] if done[b] < lens[b] else -1
+        eng.pending.copy_(torch.from_numpy(toks[:, 0].copy()))
+        draft = torch.from_numpy(toks[:, 1:].copy()).to(eng.dev)
+        fl = torch.from_numpy(force).to(eng.dev)
+        _, ids = eng.sf_verify_step(k, draft, logits=False)
+        eng.sf_accept_commit(k, draft, ids, force_len=fl)
+        eng.len_upper = int(done.max())
+        if step < total - 1:
+            # pending of a finished block is the next prompt token, not the target's choice
+            pend = eng.pending.cpu().numpy()
+            pend[nxt >= 0] = nxt[nxt >= 0]
+            eng.pending.copy_(torch.from_numpy(pend))
+        if k_draft > 0 and eng._D is not None:
+            eng.sf_draft_step(k_draft)
+    return eng.pending.clone()

@@ -58,11 +58,12 @@ def test_create_validates_arguments():
     assert create(cfg(), cfg(n_layers=1, d_ffn=512))[0] == sfb.SF_EINVAL    # widths must agree
     assert create(cfg(n_q_heads=6), cfg(n_layers=1, n_q_heads=6))[0] == sfb.SF_EINVAL   # Hq % Hkv
     assert create(cfg(), cfg(n_layers=1), B=0)[0] == sfb.SF_EINVAL
-    assert create(cfg(), cfg(n_layers=1), k=16)[0] == sfb.SF_EINVAL
+    assert create(cfg(), cfg(n_layers=1), k=128)[0] == sfb.SF_EINVAL
     bf = dict(dtype=sfb.SF_BF16, head_dim=96, d_model=384)
     assert create(cfg(**bf), cfg(n_layers=1, **bf))[0] == sfb.SF_EUNSUPPORTED   # bf16 head_dim
     wide = dict(dtype=sfb.SF_BF16, n_q_heads=32, n_kv_heads=2, head_dim=64, d_model=2048)
-    assert create(cfg(**wide), cfg(n_layers=1, **wide), k=4)[0] == sfb.SF_EUNSUPPORTED  # 16*5 rows > 64
+    assert create(cfg(**wide), cfg(n_layers=1, **wide), k=4)[0] == sfb.SF_OK
+    assert create(cfg(**wide), cfg(n_layers=1, **wide), k=64)[0] == sfb.SF_EUNSUPPORTED  # 16*65 rows > 1024
 
 
 def test_steps_reject_bad_state_before_launching_anything():
@@ -141,7 +142,7 @@ def test_rope_attention_op_validates_before_launching_anything():
     assert call(upper=124) == sfb.SF_ECAPACITY         # 124 + 5 > 128
     assert call(ws_bytes=need - 1) == sfb.SF_ECAPACITY
     assert call(ws=fake + 16) == sfb.SF_ECAPACITY      # misaligned workspace
-    assert call(n_q=17) == sfb.SF_EUNSUPPORTED         # 4 query heads per kv head x 17 rows > 64
+    assert call(n_q=257, cap=512, upper=100) == sfb.SF_EUNSUPPORTED   # 4 query heads per kv head x 257 rows > 1024
     L.sf_destroy(ctx)
     st, ctx32 = create(cfg(), cfg(n_layers=1))         # fp32 keeps the two separate kernels
     assert st == sfb.SF_OK

@@ -335,3 +335,46 @@ def test_accept_commit_wants_the_block_that_was_just_verified():
         eng.sf_accept_commit(k, draft, ids)                              # nothing left to commit
     assert e.value.status == sfb.SF_ESTATE
     assert torch.equal(eng.kv_len, len0 + acc)                          # and nothing was enqueued
+
+
+@pytest.mark.parametrize("name,block", [("tiny", 24), ("8b-slice", 64), ("1b-slice", 128)])
+def test_prefill_in_large_blocks(name, block):
+    """Chunked prefill with blocks far longer than the decoding block (a helper engine built for the block
+    length, same weights and caches) against the oracle's one-pass prefill: first emitted token, lengths, both
+    caches, and the first speculative step after the hand-over."""
+    m = synth.TINY if name == "tiny" else SLICES[name]
+    bf = m.dtype == "bf16"
+    tol = 2e-2 if bf else 1e-4
+    B, k, seed, cap = 4, 4, 41, 512
+    lens = [300, 77, 129, 5]                                      # several blocks, a ragged first block, one short prompt
+    prompts = synth.prompts(lens, m.vocab, seed)
+    ref, eng, _, _ = make_pair(m, B, cap, k, seed, std=0.05, round_bf16=False)
+    first_o = ref.prefill(prompts)
+    first_g = eng.prefill(prompts, block=block).cpu().numpy()
+    np.testing.assert_array_equal(eng.kv_len.cpu().numpy(), ref.kv_len)
+    if not bf:
+        np.testing.assert_array_equal(first_g, first_o)
+    else:
+        assert (first_g == first_o).mean() >= 0.75
+    last = m.n_layers - 1
+    for which, layer, src in (("tk", 0, ref.tk[0]), ("tv", 0, ref.tv[0]), ("tk", last, ref.tk[last])):
+        got = to_np(eng.sf_kv_export(which, layer))
+        for b in range(B):
+            assert rel_err(got[b, :, :lens[b]], src[b, :, :lens[b]]) < tol, which
+    # the draft cache: the oracle fills it in its first draft step (all prompt rows are "new" to it)
+    ref.pending[:] = first_g                                     # same pending token on both sides
+    d_o, dl_o = ref.draft_step(k, want_logits=True)
+    got = to_np(eng.sf_kv_export("dk"))
+    for b in range(B):
+        assert rel_err(got[b, :, :lens[b]], ref.dk[b, :, :lens[b]]) < tol
+    # The step after the hand-over runs free (its inputs are the GPU's own prefill results, each within tol of
+    # the oracle's), so its outputs carry the accumulated difference: 3 tol in bf16.  A wrong hand-over (another
+    # hooked row, a stale length) would be off by the size of the logits themselves.
+    free = 3 * tol if bf else tol
+    dl_g = torch.empty(B, k, m.vocab, dtype=torch.float32, device="cuda")
+    eng.sf_draft_step(k, logits_out=dl_g)
+    assert rel_err(to_np(dl_g), dl_o) < free
+    draft = np.random.default_rng(1).integers(0, m.vocab, (B, k)).astype(np.int32)
+    lg_o = ref.verify_step(k, draft)
+    lg_g, _ = eng.sf_verify_step(k, torch.from_numpy(draft).cuda())
+    assert rel_err(to_np(lg_g), lg_o) < free

@@ -39,10 +39,12 @@ def run_attention(dtype, B, nq, Hq, Hkv, hd, cap, lens, mode, seed=1, poison=Fal
 
 @pytest.mark.parametrize("mode", [sfb.SF_MASK_CAUSAL, sfb.SF_MASK_BIDIR])
 @pytest.mark.parametrize("Hq,Hkv,hd,nq", [(8, 2, 128, 5), (10, 2, 128, 5), (8, 2, 64, 5), (8, 2, 128, 7),
-                                          (4, 4, 128, 1), (16, 2, 128, 5)])
+                                          (4, 4, 128, 1), (16, 2, 128, 5),
+                                          # blocks of many rows (k = 8; prefill blocks): several 32-row tiles
+                                          (8, 2, 128, 9), (8, 2, 64, 33), (8, 2, 128, 64), (10, 2, 128, 64)])
 def test_attention_bf16_ragged(mode, Hq, Hkv, hd, nq):
     # lengths span: empty prefix, inside one tile, tile boundary, several chunks + ragged tail
-    lens = [0, 27, 32, 1500, 511, 2000]
+    lens = [0, 27, 32, 1500, 511, min(2000, 2048 - nq)]
     got, ref = run_attention("bf16", 6, nq, Hq, Hkv, hd, 2048, lens, mode)
     assert np.all(np.isfinite(got))
     assert rel_err(got, ref) < BF16_TOL
@@ -309,7 +311,8 @@ def test_lm_head_fused_argmax_bit_exact(dtype, M, V):
 
 @pytest.mark.parametrize("mode", [sfb.SF_MASK_CAUSAL, sfb.SF_MASK_BIDIR])
 @pytest.mark.parametrize("Hq,Hkv,hd,nq,chunk", [(8, 2, 64, 5, 0), (8, 2, 128, 5, 0), (16, 2, 128, 5, 0),
-                                                 (8, 2, 64, 5, 16), (8, 2, 128, 7, 16), (4, 4, 128, 1, 0)])
+                                                 (8, 2, 64, 5, 16), (8, 2, 128, 7, 16), (4, 4, 128, 1, 0),
+                                                 (8, 2, 128, 33, 0), (8, 2, 64, 64, 16)])
 def test_rope_attention_fused(mode, Hq, Hkv, hd, nq, chunk):
     """The target layers' kernel (rotate Q and K, append K and V, attend) against the oracle's rope +
     attention and, bit for bit, against the two separate kernels.  Lengths: empty prefix, a block that
