@@ -110,7 +110,7 @@ def cpu_baseline(wl, seed, budget_s=25.0):
         orc.n_new[:] = 1
         orc.pending[:] = g.integers(0, m.vocab, Bp)
         steps, tokens, t_used = 0, 0, 0.0
-        while steps < 1 or (t_used < budget and steps < 4 and t_used / steps * (steps + 1) < budget):
+        while steps < 1 or (t_used < budget and steps < 12 and t_used / steps * (steps + 1) < budget):
             t1 = time.time()
             d = orc.draft_step(k)
             lg = orc.verify_step(k, d)

@@ -3,7 +3,8 @@ import ctypes as C
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libspecformer.so")
+# SF_LIB in the environment names a library built elsewhere (the host-sanitizer run of the ABI tests)
+LIB_PATH = os.environ.get("SF_LIB") or os.path.join(HERE, "libspecformer.so")
 
 SF_OK, SF_EINVAL, SF_ECAPACITY, SF_ESTATE, SF_EHIP, SF_EUNSUPPORTED = range(6)
 SF_BF16, SF_F32 = 0, 1

@@ -35,5 +35,18 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+def build_host_sanitized(out: str) -> str:
+    """The same library with AddressSanitizer + UBSan on the HOST side only (argument checking, workspace
+    planning, launch glue); device code is built as usual.  For the CPU-only ABI tests."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in FLAGS if f != "-O3"] + ["-O1", "-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host",
+                                                "-fsanitize=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+    cmd = [hipcc] + flags + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", out]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+    return out
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose=True))

@@ -52,7 +52,7 @@ def main():
     Bs = [int(x) for x in args.batches.split(",")]
     qs = sorted(int(x) for x in args.blocks.split(","))
     G = m.n_q_heads // m.n_kv_heads
-    qs = [q for q in qs if m.dtype != "bf16" or G * q <= 64]
+    qs = [q for q in qs if m.dtype != "bf16" or G * q <= 1024]
     torch.cuda.set_device(0)
     tw, _ = synth.device_weights(m, 1, wl.seed)
     rows, shared = [], None
