@@ -186,6 +186,17 @@ sf_status sf_accept_commit(sf_ctx *ctx, const sf_state *st, int32_t k, const int
                            const int32_t *target_ids, const int32_t *force_len, int32_t *accept_len,
                            int32_t *out_tokens, void *stream);
 
+/* What the device saw that contradicts the host's promises.  The step calls size their launch grids from
+ * host_len_upper and never read lengths back, so a kv_len[b] above that bound (the tail of that sequence is
+ * then not attended to, and nothing reports it) or a block that does not fit the cache (lengths are clamped
+ * to cap - block, older rows get overwritten) cannot fail synchronously.  Instead the first kernel of
+ * sf_verify_step and sf_draft_step ORs SF_DEVERR_* bits into a sticky word inside the workspace, and this
+ * call reads it back: it WAITS for `stream`, copies the word to *flags (host), clears it, and returns
+ * SF_ECAPACITY when any bit was set, SF_OK otherwise.  A caller that replays a captured step with a pinned
+ * bound must stop before kv_len can reach cap - (k+1), and may poll this call to be sure. */
+enum { SF_DEVERR_LEN_ABOVE_BOUND = 1, SF_DEVERR_CACHE_FULL = 2 };
+sf_status sf_check_state(const sf_ctx *ctx, const sf_state *st, int32_t *flags, void *stream);
+
 /* Plain <-> tiled K/V layout, one layer: plain is dev elem [B][Hkv][cap][hd]; `tiled` points at
  * the layer's slab inside a cache buffer: (char*)cache + layer * sf_kv_cache_bytes(ctx,1,B,cap).
  * is_v selects the V tiling (K and V are tiled differently). */

@@ -15,7 +15,7 @@ KERNEL_CLASSES = ["linear", "attention", "attention_combine", "rmsnorm", "rope_k
 
 EXPORTS = [
     "sf_create", "sf_destroy", "sf_workspace_bytes", "sf_kv_cache_bytes", "sf_bind", "sf_draft_step",
-    "sf_verify_step", "sf_accept_commit", "sf_kv_import", "sf_kv_export", "sf_attention_workspace_bytes",
+    "sf_verify_step", "sf_accept_commit", "sf_check_state", "sf_kv_import", "sf_kv_export", "sf_attention_workspace_bytes",
     "sf_op_attention", "sf_packed_weight_bytes", "sf_pack_weight", "sf_linear_workspace_bytes", "sf_op_linear",
     "sf_op_rmsnorm_linear", "sf_op_linear_swiglu", "sf_linear_argmax_workspace_bytes", "sf_op_linear_argmax",
     "sf_op_rmsnorm", "sf_op_rope_kv_append", "sf_rope_attention_workspace_bytes", "sf_op_rope_attention",
@@ -84,6 +84,7 @@ def lib():
     L.sf_draft_step.argtypes = [vp, P(State), i32, i32, i32, vp, vp, vp]
     L.sf_verify_step.argtypes = [vp, P(State), i32, vp, i32, vp, vp, vp]
     L.sf_accept_commit.argtypes = [vp, P(State), i32, vp, vp, vp, vp, vp, vp]
+    L.sf_check_state.argtypes = [vp, P(State), P(i32), vp]
     L.sf_op_accept.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.sf_linear_argmax_workspace_bytes.argtypes = [vp, i32, i32]
     L.sf_linear_argmax_workspace_bytes.restype = sz

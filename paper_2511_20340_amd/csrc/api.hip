@@ -51,7 +51,7 @@ struct Arena {
   size_t h, hb, a, qkv, qr, ao, gu, act, table, order, part_o, part_ml, pmax, pidx, logits;  // shared
   size_t f4, x, kvc, xl, s0, s0b;                                        // draft only
   size_t x_last, id_last, q1, qr1, ao1, len_m1, zeros, kc2, vc2;         // draft, two-stage wiring
-  size_t gemm_ws, gemm_ws_bytes;
+  size_t gemm_ws, gemm_ws_bytes, dev_err;
   size_t total;
 };
 
@@ -71,6 +71,7 @@ Arena plan(const sf_ctx *c, int B, int k, int cap) {
   a.gemm_ws_bytes = m.dtype == SF_BF16 ? gemm_workspace_bytes((int)Mx) : 0;
   a.gemm_ws = take(a.gemm_ws_bytes);
   a.zeros = take((size_t)B * sizeof(int32_t));  // likewise never written: the empty prefix of a slot-only attention
+  a.dev_err = take(sizeof(int32_t));            // sticky SF_DEVERR_* bits, read and cleared by sf_check_state
   a.h = take(M * d * sizeof(float));  // the residual stream
   a.hb = take(m.dtype == SF_BF16 ? M * d * es : 0);
   a.a = take(Mx * d * es);
@@ -394,6 +395,7 @@ sf_status sf_verify_step(sf_ctx *c, const sf_state *st, int32_t k, const int32_t
   // the sequences by length, and the attention launches of this call start the longest first
   const int attn_groups = B * m.n_kv_heads * ((m.n_q_heads / m.n_kv_heads * q + 31) / 32);
   ra.order = bf && attn_groups > 512 ? (int32_t *)(ws + A.order) : nullptr;
+  ra.dev_err = (int32_t *)(ws + A.dev_err); ra.len_upper = len_upper;
   LAUNCH(K_ROPE, launch_rope_table(ra, r.s));
   const size_t lb = kv_layer_bytes(m, B, cap);
   for (int l = 0; l < L && r.st == SF_OK; ++l) {
@@ -502,6 +504,7 @@ sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, 
   norm_gemm(r, m, s0, s0b, norm_s, a, wqkv_s, qkv, Ms, nq + 2 * nkv, d, 0);
   ra.qkv = qkv; ra.q_out = qr; ra.kc = (void *)kc_s; ra.vc = (void *)vc_s; ra.kv_len = len_s; ra.n_new = nullptr;
   ra.n_q = k; ra.cap = cap_s; ra.kv_only = 0; ra.pos_mode = 0;
+  if (!two_stage) { ra.dev_err = (int32_t *)(ws + A.dev_err); ra.len_upper = len_upper; }
   LAUNCH(K_ROPE, launch_rope_table(ra, r.s));
   LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
   attention(r, m, qr, kc_s, vc_s, len_s, ao, part_o, part_ml, B, k, cap_s, mask, len_upper_s);
@@ -541,6 +544,23 @@ sf_status sf_op_accept(const sf_ctx *c, int32_t B, int32_t k, const int32_t *dra
   AcceptArgs a{target_ids, draft, force_len, accept_len, out_tokens, kv_len, pending, n_new, cu_new, B, k};
   LAUNCH(K_ACCEPT, launch_accept(a, r.s));
   return r.st;
+}
+
+sf_status sf_check_state(const sf_ctx *c, const sf_state *st, int32_t *flags, void *stream) {
+  if (!c || !st || !flags || !st->workspace || st->B < 1 || st->B > c->max_B || st->cap < TK || st->cap % TK)
+    return SF_EINVAL;
+  const Arena A = plan(c, st->B, 0, st->cap);  // the word sits in the k-independent head of the arena
+  if (st->workspace_bytes < A.dev_err + sizeof(int32_t)) return SF_ECAPACITY;
+  int32_t *word = (int32_t *)((char *)st->workspace + A.dev_err);
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t e = hipMemcpyAsync(flags, word, sizeof(int32_t), hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e == hipSuccess && *flags != 0) {
+    e = hipMemsetAsync(word, 0, sizeof(int32_t), s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+  }
+  if (e != hipSuccess) { c->hip_err = (int)e; return SF_EHIP; }
+  return *flags ? SF_ECAPACITY : SF_OK;
 }
 
 sf_status sf_kv_import(const sf_ctx *c, const void *plain, void *tiled, int32_t is_v, int32_t B, int32_t cap,

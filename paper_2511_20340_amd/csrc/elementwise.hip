@@ -116,7 +116,19 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const TI *__restrict__ X, 
 // the tail of a ragged batch.
 __global__ void rope_table_kernel(float2 *__restrict__ table, const int32_t *__restrict__ kv_len,
                                   const int32_t *__restrict__ n_new, int B, int n_q, int half, int pos_mode,
-                                  double log2_theta, int32_t *__restrict__ order) {
+                                  double log2_theta, int32_t *__restrict__ order, int32_t *__restrict__ dev_err,
+                                  int len_upper, int cap) {
+  if (dev_err && blockIdx.x == 0) {
+    // the launch grids of this step were sized from the host's bound: say so if a length breaks it
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+      const int len = kv_len[b];
+      int bits = 0;
+      if (pos_mode == 0 && len > len_upper) bits |= SF_DEVERR_LEN_ABOVE_BOUND;
+      if (pos_mode == 0 && len + n_q > cap) bits |= SF_DEVERR_CACHE_FULL;
+      if (len < 0) bits |= SF_DEVERR_LEN_ABOVE_BOUND;
+      if (bits) atomicOr(dev_err, bits);
+    }
+  }
   if (order && blockIdx.x == gridDim.x - 1) {
     for (int b = threadIdx.x; b < B; b += blockDim.x) {
       const int mine = kv_len[b];
@@ -305,7 +317,8 @@ hipError_t launch_rope_table(const RopeArgs &a, hipStream_t s) {
   const int half = a.hd / 2;
   const int n = a.B * a.n_q * half;
   rope_table_kernel<<<(n + 255) / 256 + (a.order ? 1 : 0), 256, 0, s>>>(a.table, a.kv_len, a.n_new, a.B, a.n_q, half,
-                                                                        a.pos_mode, log2((double)a.theta), a.order);
+                                                                        a.pos_mode, log2((double)a.theta), a.order,
+                                                                        a.dev_err, a.len_upper, a.cap);
   return hipGetLastError();
 }
 

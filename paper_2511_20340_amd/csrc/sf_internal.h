@@ -164,6 +164,10 @@ struct RopeArgs {
   const int32_t *n_new;  // pos_mode 1
   float2 *table;         // [M][hd/2] cos,sin scratch
   int32_t *order;        // optional [B]: filled with the sequences in descending kv_len order
+  // optional: a sticky word that collects SF_DEVERR_* bits when a device-side length contradicts what the
+  // host promised (len_upper >= every kv_len, kv_len + n_q <= cap)
+  int32_t *dev_err = nullptr;
+  int len_upper = 0;
   int B, n_q, Hq, Hkv, hd, cap;
   int kv_only;   // rows carry only K,V
   int pos_mode;  // 0: pos = kv_len[b]+i, all rows valid; 1: pos = kv_len[b]-n_new[b]+i, valid iff i<n_new[b]

@@ -192,6 +192,14 @@ class Engine:
             self.len_upper = min(self.len_upper + k + 1, self.cap)
         return acc, out
 
+    def sf_check_state(self):
+        """-> SF_DEVERR_* bits the device collected since the last check (0 = none); waits for the stream."""
+        flags = C.c_int32(0)
+        st = self.lib.sf_check_state(self.ctx, C.byref(self.st), C.byref(flags), _stream())
+        if st not in (sfb.SF_OK, sfb.SF_ECAPACITY):
+            sfb.check(st, "sf_check_state", self.ctx)
+        return flags.value
+
     def sf_op_accept(self, k, draft, target_ids, force_len=None):
         """The acceptance rule alone on this engine's state arrays (no call-order check)."""
         acc = torch.empty(self.B, dtype=torch.int32, device=self.dev)

@@ -378,3 +378,26 @@ def test_prefill_in_large_blocks(name, block):
     lg_o = ref.verify_step(k, draft)
     lg_g, _ = eng.sf_verify_step(k, torch.from_numpy(draft).cuda())
     assert rel_err(to_np(lg_g), lg_o) < free
+
+
+@pytest.mark.parametrize("name", ["tiny", "1b-slice"])
+def test_device_lengths_that_break_the_host_bound_are_reported(name):
+    """The step calls trust host_len_upper; a device length above it (or a block that no longer fits the cache)
+    cannot fail synchronously, so the first kernel records it and sf_check_state reports and clears it.  The
+    kernels clamp what they read and write to the slab, so the condition is safe to provoke from the host."""
+    m = synth.TINY if name == "tiny" else SLICES[name]
+    B, k, cap = 3, 4, 64
+    _, eng, _, _ = make_pair(m, B, cap, k, 5, std=0.05)
+    eng.prefill(synth.prompts([6, 9, 12], m.vocab, 5))
+    assert eng.sf_check_state() == 0
+    draft = torch.zeros(B, k, dtype=torch.int32, device="cuda")
+    eng.sf_verify_step(k, draft)
+    assert eng.sf_check_state() == 0                               # an honest bound: nothing to report
+    eng.kv_len.copy_(torch.tensor([6, 30, 12], dtype=torch.int32)) # sequence 1 is longer than the host believes
+    eng.len_upper = 12
+    eng.sf_verify_step(k, draft)
+    assert eng.sf_check_state() == 1                               # SF_DEVERR_LEN_ABOVE_BOUND
+    assert eng.sf_check_state() == 0                               # read once, then cleared
+    eng.kv_len.copy_(torch.tensor([6, cap - 2, 12], dtype=torch.int32))   # and now the block does not fit either
+    eng.sf_draft_step(k)
+    assert eng.sf_check_state() == 3                               # both bits, from the draft step's first kernel
