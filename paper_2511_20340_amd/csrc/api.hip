@@ -80,7 +80,7 @@ Arena plan(const sf_ctx *c, int B, int k, int cap) {
   a.ao = take(M * nq * es);
   a.gu = take(m.dtype == SF_F32 ? M * 2 * F * sizeof(float) : 0);  // bf16 gates in the GEMM epilogue
   a.act = take(M * F * es);
-  a.table = take(Mx * (m.head_dim / 2) * sizeof(float2));
+  a.table = take((Mx + Ms) * (m.head_dim / 2) * sizeof(float2));  // block rows, then the draft's slot rows
   a.order = take((size_t)B * sizeof(int32_t));
   const int G = m.n_q_heads / m.n_kv_heads;
   size_t part = m.dtype == SF_BF16 ? attn_workspace_bytes(B, m.n_kv_heads, m.head_dim, G, k + 1, cap) : 0;
@@ -466,8 +466,15 @@ sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, 
   ra.table = (float2 *)(ws + A.table);
   ra.B = B; ra.n_q = qm; ra.Hq = m.n_q_heads; ra.Hkv = m.n_kv_heads; ra.hd = m.head_dim; ra.cap = cap;
   ra.kv_only = 1; ra.pos_mode = 1; ra.theta = m.rope_theta;
+  // the same launch fills the slots' table (positions kv_len[b] + s) when they sit behind the cached context
+  float2 *slot_table = ra.table + (size_t)Mh * (m.head_dim / 2);
+  if (!two_stage) {
+    ra.table2 = slot_table; ra.n_q2 = k;
+    ra.dev_err = (int32_t *)(ws + A.dev_err); ra.len_upper = len_upper;
+  }
   LAUNCH(K_ROPE, launch_rope_table(ra, r.s));
   LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
+  ra.table2 = nullptr; ra.dev_err = nullptr;
   const void *norm_s = w.attn_norm, *wqkv_s = w.wqkv, *wo_s = w.wo;  // the slot attention's parameters
   const void *kc_s = st->dk, *vc_s = st->dv;
   const int32_t *len_s = st->kv_len;
@@ -503,11 +510,12 @@ sf_status sf_draft_step(sf_ctx *c, const sf_state *st, int32_t k, int32_t mask, 
   // one attention + SwiGLU layer over the slots
   norm_gemm(r, m, s0, s0b, norm_s, a, wqkv_s, qkv, Ms, nq + 2 * nkv, d, 0);
   ra.qkv = qkv; ra.q_out = qr; ra.kc = (void *)kc_s; ra.vc = (void *)vc_s; ra.kv_len = len_s; ra.n_new = nullptr;
-  ra.n_q = k; ra.cap = cap_s; ra.kv_only = 0; ra.pos_mode = 0;
-  if (!two_stage) { ra.dev_err = (int32_t *)(ws + A.dev_err); ra.len_upper = len_upper; }
-  LAUNCH(K_ROPE, launch_rope_table(ra, r.s));
-  LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
-  attention(r, m, qr, kc_s, vc_s, len_s, ao, part_o, part_ml, B, k, cap_s, mask, len_upper_s);
+  ra.n_q = k; ra.cap = cap_s; ra.kv_only = 0; ra.pos_mode = 0; ra.table = slot_table;
+  if (two_stage) LAUNCH(K_ROPE, launch_rope_table(ra, r.s));  // slots at positions 0..k-1 of their own tile
+  // bf16: the attention kernel rotates the slots' Q and K and appends their K, V rows itself
+  if (!bf) LAUNCH(K_ROPE, launch_rope_kv(ra, m.dtype, r.s));
+  attention(r, m, qr, kc_s, vc_s, len_s, ao, part_o, part_ml, B, k, cap_s, mask, len_upper_s, bf ? qkv : nullptr,
+            ra.table);
   ex.res_f32 = 1;
   gemm(r, m.dtype, ao, wo_s, nullptr, s0, s0, Ms, d, nq, 1, 0, 0, 0.f, &ex);
   norm_swiglu_in(r, m, s0, s0b, w.ffn_norm, a, w.w_gate_up, gu, act, Ms, F, d);

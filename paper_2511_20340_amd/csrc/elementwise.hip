@@ -114,17 +114,20 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const TI *__restrict__ X, 
 // One extra workgroup (when `order` is given) ranks the sequences by descending length, ties by
 // index: order[rank] = b.  The attention kernel starts the longest sequences first, which evens out
 // the tail of a ragged batch.
+// A second table (table2: n_q2 rows per sequence at positions kv_len[b] + r) can be filled by the same launch.
 __global__ void rope_table_kernel(float2 *__restrict__ table, const int32_t *__restrict__ kv_len,
                                   const int32_t *__restrict__ n_new, int B, int n_q, int half, int pos_mode,
                                   double log2_theta, int32_t *__restrict__ order, int32_t *__restrict__ dev_err,
-                                  int len_upper, int cap) {
+                                  int len_upper, int cap, float2 *__restrict__ table2, int n_q2) {
   if (dev_err && blockIdx.x == 0) {
     // the launch grids of this step were sized from the host's bound: say so if a length breaks it
+    const bool fwd = pos_mode == 0 || table2;        // rows that extend the sequences are part of this launch
+    const int rows = table2 ? n_q2 : n_q;
     for (int b = threadIdx.x; b < B; b += blockDim.x) {
       const int len = kv_len[b];
       int bits = 0;
-      if (pos_mode == 0 && len > len_upper) bits |= SF_DEVERR_LEN_ABOVE_BOUND;
-      if (pos_mode == 0 && len + n_q > cap) bits |= SF_DEVERR_CACHE_FULL;
+      if (fwd && len > len_upper) bits |= SF_DEVERR_LEN_ABOVE_BOUND;
+      if (fwd && len + rows > cap) bits |= SF_DEVERR_CACHE_FULL;
       if (len < 0) bits |= SF_DEVERR_LEN_ABOVE_BOUND;
       if (bits) atomicOr(dev_err, bits);
     }
@@ -141,8 +144,13 @@ __global__ void rope_table_kernel(float2 *__restrict__ table, const int32_t *__r
     }
     return;
   }
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= B * n_q * half) return;
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  const int n1 = B * n_q * half;
+  if (idx >= n1) {  // the second table, if any
+    idx -= n1;
+    if (!table2 || idx >= B * n_q2 * half) return;
+    table = table2; n_q = n_q2; pos_mode = 0;
+  }
   const int i = idx % half, row = idx / half, b = row / n_q, r = row % n_q;
   const int pos = pos_mode == 0 ? kv_len[b] + r : kv_len[b] - n_new[b] + r;
   const double inv_freq = exp2(-(double)(2 * i) / (double)(2 * half) * log2_theta);
@@ -315,10 +323,10 @@ hipError_t launch_rmsnorm(const NormArgs &a, int dtype, hipStream_t s) {
 
 hipError_t launch_rope_table(const RopeArgs &a, hipStream_t s) {
   const int half = a.hd / 2;
-  const int n = a.B * a.n_q * half;
+  const int n = a.B * (a.n_q + (a.table2 ? a.n_q2 : 0)) * half;
   rope_table_kernel<<<(n + 255) / 256 + (a.order ? 1 : 0), 256, 0, s>>>(a.table, a.kv_len, a.n_new, a.B, a.n_q, half,
                                                                         a.pos_mode, log2((double)a.theta), a.order,
-                                                                        a.dev_err, a.len_upper, a.cap);
+                                                                        a.dev_err, a.len_upper, a.cap, a.table2, a.n_q2);
   return hipGetLastError();
 }
 

@@ -163,6 +163,8 @@ struct RopeArgs {
   const int32_t *kv_len;
   const int32_t *n_new;  // pos_mode 1
   float2 *table;         // [M][hd/2] cos,sin scratch
+  float2 *table2 = nullptr;  // optional second table of the same launch: n_q2 rows per sequence at kv_len[b] + r
+  int n_q2 = 0;
   int32_t *order;        // optional [B]: filled with the sequences in descending kv_len order
   // optional: a sticky word that collects SF_DEVERR_* bits when a device-side length contradicts what the
   // host promised (len_upper >= every kv_len, kv_len + n_q <= cap)
