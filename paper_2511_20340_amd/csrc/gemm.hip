@@ -86,9 +86,10 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const Epilogu
     // agent-scope atomic accesses only (write-through stores, loads that bypass the caches), so no
     // cache-wide write-back or invalidate is needed for them.  Hand-over: every wave waits until its
     // stores are acknowledged and releases at workgroup scope, the workgroup meets at a barrier, and one
-    // thread takes the tile's ticket with an acquire-release read-modify-write at agent scope; that
-    // chain (workgroup release -> barrier -> agent acq_rel ticket ... agent acq_rel ticket -> barrier)
-    // orders every split's stores before the loads of the workgroup that draws the last ticket.
+    // thread takes the tile's ticket with a release read-modify-write at agent scope; the thread that
+    // draws the last ticket follows it with an acquire fence at agent scope.  That chain (workgroup
+    // release -> barrier -> agent release ticket ... last ticket -> agent acquire fence -> barrier)
+    // orders every split's stores before the loads of the workgroup that finishes the tile.
     const size_t tile = (size_t)tn * tiles_m + tm;
     constexpr size_t PER_WAVE = (size_t)TM * TN * 64 * 16;
     float *mine = partial + ((tile * split_k + ks) * NW + wave) * PER_WAVE;
@@ -106,7 +107,11 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const Epilogu
     __builtin_amdgcn_s_waitcnt(0);  // all counters: this wave's write-through stores have been acknowledged
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
-    if (tid == 0) s_ticket = __hip_atomic_fetch_add(&tickets[tile], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) {
+      s_ticket = __hip_atomic_fetch_add(&tickets[tile], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+      // only the workgroup that draws the last ticket reads other workgroups' data: it alone acquires
+      if (s_ticket == (unsigned)(split_k - 1)) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    }
     __syncthreads();
     if (s_ticket != (unsigned)(split_k - 1)) return;  // not the last split of this tile
 #pragma unroll
@@ -224,8 +229,24 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const Epilogu
   }
 
   // epilogue: lane holds column ln, rows c_row(v, lh) of every 32x32 tile.  y may be the residual
-  // buffer itself, so the block's residual values are all fetched before its first store (one wait
-  // per block instead of one per element).
+  // buffer itself, and the residual loads are the only latency left at this point: ALL of the wave's
+  // residual values are requested before its first store (one exposed round trip per wave).
+  float res[TM][TN][16];
+  if (e.residual) {
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+      for (int b = 0; b < TN; ++b) {
+        const int col = min((nb0 + b) * 32 + ln, N - 1);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = min(m0 + a * 32 + c_row(v, lh), M - 1);
+          const size_t o = (size_t)row * N + col;
+          res[a][b][v] = e.res_f32 ? reinterpret_cast<const float *>(e.residual)[o]
+                                   : bf2f(reinterpret_cast<const bf16_t *>(e.residual)[o]);
+        }
+      }
+  }
 #pragma unroll
   for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -233,23 +254,13 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const Epilogu
       const int col = (nb0 + b) * 32 + ln;
       if (col >= N) continue;
       const float bv = e.bias ? bf2f(e.bias[col]) : 0.f;
-      float res[16];
-      if (e.residual) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = min(m0 + a * 32 + c_row(v, lh), M - 1);
-          const size_t o = (size_t)row * N + col;
-          res[v] = e.res_f32 ? reinterpret_cast<const float *>(e.residual)[o]
-                             : bf2f(reinterpret_cast<const bf16_t *>(e.residual)[o]);
-        }
-      }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = m0 + a * 32 + c_row(v, lh);
         if (row >= M) continue;
         float r = acc[a][b][v] + bv;
         const size_t o = (size_t)row * N + col;
-        if (e.residual) r += res[v];
+        if (e.residual) r += res[a][b][v];
         if (e.out_f32) reinterpret_cast<float *>(e.y)[o] = r;
         else reinterpret_cast<bf16_t *>(e.y)[o] = f2bf(r);
         if (e.y2) e.y2[o] = f2bf(r);
