@@ -527,7 +527,7 @@ constexpr int TILE_TM[N_TILES + 1] = {0, 1, 2, 3, 4, 5, 2, 3, 4, 5, 5};
 // M-tiles and the activation re-reads of the column tiles count; ~224 workgroups fill the chip;
 // splitting K costs a partial-tile round trip and a serial tail, so it is used only when the
 // unsplit grid is too small and K is long.
-constexpr int WG_FULL = 224, WG_SPLIT = 192;
+constexpr int WG_FULL = 224, WG_SPLIT = 160;
 constexpr size_t REREAD_CAP = 384u << 20;
 
 int pow2floor(int v) { int p = 1; while (p * 2 <= v) p *= 2; return p; }
@@ -536,21 +536,24 @@ int pow2floor(int v) { int p = 1; while (p * 2 <= v) p *= 2; return p; }
 // operand traffic per compute unit, MFMA time per compute unit, how evenly the workgroups divide over
 // 256 CUs and the cost of splitting K, and a cost model ranks the candidates better than rules.  Per
 // workgroup: operand bytes (BM + BN) * K/split * 2 and 2 * BM * BN * K/split flop; a CU works through
-// ceil(workgroups / 256) of them at ~80 GB/s of operand intake and ~5.5 TFLOP/s, the two overlapping
-// for about two thirds; ~10 us of launch and drain, ~10 us per extra K split.  The constants and the
-// per-tile factors are least-squares fits to sweeps of all tiles x splits over the 8B shapes at 768 and
-// 1280 rows and the 14B shapes at 640 rows on MI355X; over those 12 shapes the model's choice is
-// within 1.3 % of the best measured configuration on average (7.5 % worst).
+// ceil(workgroups / 256) of them at ~88 GB/s of operand intake and ~9.5 TFLOP/s, the two hardly
+// overlapping (the shorter one counts for 86 %); ~8 us of launch and drain; a split costs ~8 us plus its
+// partial tiles (M * N * 4 * split bytes) at ~1.1 TB/s.  The constants and the per-tile factors were
+// searched for the smallest regret of the choice, with the model's own error held at 13 % rms, over
+// sweeps of all tiles x splits {1,2,4} (medians of interleaved repeats) of 30 shapes on MI355X: the 8B
+// layers at 384 ... 1792 rows, the 14B layers at 448 ... 896 rows and the two LM heads.  Over those the
+// model's choice is within 0.5 % of the best measured configuration on average (6.7 % worst).
 double model_us(int M, int N, int K, int tile, int split) {
-  static const double factor[N_TILES + 1] = {0, 0.9, 0.889, 0.945, 1.013, 1.068, 0.95, 1.044, 0.945, 0.943, 1.003};
+  static const double factor[N_TILES + 1] = {0, 1.0, 1.022, 1.005, 1.039, 1.121, 1.0, 0.947, 0.887, 0.938, 1.278};
   const int BM = TILE_TM[tile] * 32, BN = tile >= 6 ? 256 : 128;
   const double tiles = (double)((M + BM - 1) / BM) * ((N + BN - 1) / BN) * split;
   const double per_cu = std::ceil(tiles / 256.0), ks = (double)K / split;
-  const double t_mem = per_cu * (BM + BN) * ks * 2.0 / 80e9;
-  const double t_mma = per_cu * 2.0 * BM * BN * ks / 5.5e12;
+  const double t_mem = per_cu * (BM + BN) * ks * 2.0 / 87.6e9;
+  const double t_mma = per_cu * 2.0 * BM * BN * ks / 9.5e12;
   const double t_hbm = (double)N * K * 2.0 / 4.7e12;
-  const double t = std::max({t_mem, t_mma, t_hbm}) + 0.35 * std::min(t_mem, t_mma);
-  return (t * 1e6 + 10.0 + 10.0 * (split - 1)) * factor[tile];
+  const double t = std::max({t_mem, t_mma, t_hbm}) + 0.86 * std::min(t_mem, t_mma);
+  const double t_split = split > 1 ? 8.1 + (double)M * N * 4.0 * split / 1.08e12 * 1e6 : 0.0;
+  return (t * 1e6 + 8.4 + t_split) * factor[tile];
 }
 
 GemmConfig pick(int M, int N, int K, size_t ws_bytes, int fixed_split);
