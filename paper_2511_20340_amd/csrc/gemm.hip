@@ -20,8 +20,9 @@
 // the partials in split order (deterministic), applies the epilogue and resets the ticket, so one
 // launch does everything and the counters stay zero between launches.
 //
-// Workgroup ids are remapped so that all M-tiles of one weight column block run on the same XCD
-// (its L2 then serves the weight units to every M-tile after one HBM read).
+// Workgroup ids are remapped so that all M-tiles of one weight column block (and K split) run on the
+// same XCD (its L2 then serves the weight units to every M-tile after one HBM read), and those units are
+// dealt evenly over the eight XCDs.
 //
 // fp32 path: plain SIMT tiling on row-major weights for the small fp32 configuration.
 #include "sf_internal.h"
@@ -293,11 +294,14 @@ __global__ __launch_bounds__(64 * NW, OCC) void gemm_ring_kernel(const bf16_t *_
   extern __shared__ __attribute__((aligned(16))) bf16_t sA[];
   __shared__ unsigned s_ticket;
 
+  // Consecutive workgroup ids go to consecutive XCDs.  The M-tiles of one (column tile, K split) unit read
+  // the same weight bytes: they get consecutive slots of ONE XCD, and the units are dealt round-robin over
+  // the XCDs, so no XCD holds more than one unit above the average.
   const int id = blockIdx.x;
   const int xcd = id % XCDS, j = id / XCDS;
-  const int tm = j % tiles_m, ks = (j / tiles_m) % split_k;
-  const int tn = (j / (tiles_m * split_k)) * XCDS + xcd;
-  if (tn >= tiles_n) return;
+  const int tm = j % tiles_m, unit = (j / tiles_m) * XCDS + xcd;
+  if (unit >= tiles_n * split_k) return;
+  const int tn = unit / split_k, ks = unit % split_k;
   const int m0 = tm * BM;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -478,12 +482,12 @@ hipError_t run_ring(const GemmArgs &a, hipStream_t s, int split, int mode) {
   const Plan p = make_plan(a.M, a.N, a.K, BM, BN, split);
   if (!plan_fits(p, BM, a.ws, a.ws_bytes)) return hipErrorInvalidValue;
   if (mode == 1) return hipSuccess;
-  const int groups = (p.tiles_n + XCDS - 1) / XCDS;
+  const int groups = (p.tiles_n * p.split_k + XCDS - 1) / XCDS;  // (column tile, K split) units per XCD
   size_t lds = (size_t)2 * BM * LDK * sizeof(bf16_t);
   unsigned *tickets = (unsigned *)a.ws;
   float *ssq_part = a.ws ? (float *)((char *)a.ws + GEMM_TICKET_BYTES) : nullptr;
   float *partial = a.ws ? (float *)((char *)a.ws + GEMM_TICKET_BYTES + GEMM_SSQ_BYTES) : nullptr;
-  const dim3 grid(groups * XCDS * p.tiles_m * p.split_k), block(64 * NW);
+  const dim3 grid(groups * XCDS * p.tiles_m), block(64 * NW);
   if (a.am_val && (p.split_k != 1 || a.am_stride < p.tiles_n)) return hipErrorInvalidValue;
   if (a.am_val && a.am_parts_out) *a.am_parts_out = p.tiles_n;
   static_assert((size_t)2 * BM * LDK * sizeof(bf16_t) >= (size_t)NW * BM * 8, "arg-max partials fit the activation tile");
