@@ -30,6 +30,8 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <type_traits>
+#include <utility>
 
 namespace sf {
 namespace {
@@ -50,6 +52,17 @@ struct Epilogue {
   int hook_mask, hook_q, hook_qmax, am_stride;
   int out_f32, res_f32, glu;
 };
+
+// f(integral_constant<0>) ... f(integral_constant<N-1>): a loop whose index is a compile-time constant in
+// every iteration
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F &&f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 // max over the 32 lanes that share (lane >> 5): quad permutes, the two row mirrors, one cross-row exchange.
 // maxNum semantics: a NaN operand is ignored.
@@ -230,49 +243,73 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const Epilogu
   }
 
   // epilogue: lane holds column ln, rows c_row(v, lh) of every 32x32 tile.  y may be the residual
-  // buffer itself, and the residual loads are the only latency left at this point: ALL of the wave's
-  // residual values are requested before its first store (one exposed round trip per wave).
-  float res[TM][TN][16];
-  if (e.residual) {
+  // buffer itself, and the residual loads are the only latency left at this point: the residual values
+  // of a group of 32x32 tiles are requested before the group's first store -- one exposed round trip per
+  // group.  A wave with up to five tiles forms one group; taller ones go five tiles at a time (their
+  // residual values would not fit the register file at once).
+  auto load_residual = [&](int a, int b, float (&res)[16]) __attribute__((always_inline)) {
+    const int col = min((nb0 + b) * 32 + ln, N - 1);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = min(m0 + a * 32 + c_row(v, lh), M - 1);
+      const size_t o = (size_t)row * N + col;
+      res[v] = e.res_f32 ? reinterpret_cast<const float *>(e.residual)[o]
+                         : bf2f(reinterpret_cast<const bf16_t *>(e.residual)[o]);
+    }
+  };
+  auto store_tile = [&](int a, int b, const f32x16 &c, const float (&res)[16]) __attribute__((always_inline)) {
+    const int col = (nb0 + b) * 32 + ln;
+    if (col >= N) return;
+    const float bv = e.bias ? bf2f(e.bias[col]) : 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = m0 + a * 32 + c_row(v, lh);
+      if (row >= M) continue;
+      float r = c[v] + bv;
+      const size_t o = (size_t)row * N + col;
+      if (e.residual) r += res[v];
+      if (e.out_f32) reinterpret_cast<float *>(e.y)[o] = r;
+      else reinterpret_cast<bf16_t *>(e.y)[o] = f2bf(r);
+      if (e.y2) e.y2[o] = f2bf(r);
+      if (e.hooks) {
+        const size_t hrow = ((size_t)(row / e.hook_q) * e.hook_qmax + row % e.hook_q) * 4;
+#pragma unroll
+        for (int g = 1; g < 4; ++g)
+          if (e.hook_mask >> g & 1) e.hooks[(hrow + g) * N + col] = f2bf(r);
+      }
+    }
+  };
+  if constexpr (TM * TN <= 5) {
+    float res[TM][TN][16];
+    if (e.residual) {
+#pragma unroll
+      for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b) load_residual(a, b, res[a][b]);
+    }
 #pragma unroll
     for (int a = 0; a < TM; ++a)
 #pragma unroll
-      for (int b = 0; b < TN; ++b) {
-        const int col = min((nb0 + b) * 32 + ln, N - 1);
+      for (int b = 0; b < TN; ++b) store_tile(a, b, acc[a][b], res[a][b]);
+  } else {
+    // constant tile indices whatever the size of the body: an unroll pragma gives up beyond a size
+    // threshold, and a run-time index into the accumulators would move them out of registers
+    constexpr int AG = TN >= 5 ? 1 : 5 / TN, GROUPS = (TM + AG - 1) / AG;
+    static_for<GROUPS>([&](auto g_c) {
+      constexpr int a0 = decltype(g_c)::value * AG, a1 = a0 + AG < TM ? a0 + AG : TM;
+      float res[AG][TN][16];
+      if (e.residual) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = min(m0 + a * 32 + c_row(v, lh), M - 1);
-          const size_t o = (size_t)row * N + col;
-          res[a][b][v] = e.res_f32 ? reinterpret_cast<const float *>(e.residual)[o]
-                                   : bf2f(reinterpret_cast<const bf16_t *>(e.residual)[o]);
-        }
+        for (int a = a0; a < a1; ++a)
+#pragma unroll
+          for (int b = 0; b < TN; ++b) load_residual(a, b, res[a - a0][b]);
       }
+#pragma unroll
+      for (int a = a0; a < a1; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b) store_tile(a, b, acc[a][b], res[a - a0][b]);
+    });
   }
-#pragma unroll
-  for (int a = 0; a < TM; ++a)
-#pragma unroll
-    for (int b = 0; b < TN; ++b) {
-      const int col = (nb0 + b) * 32 + ln;
-      if (col >= N) continue;
-      const float bv = e.bias ? bf2f(e.bias[col]) : 0.f;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = m0 + a * 32 + c_row(v, lh);
-        if (row >= M) continue;
-        float r = acc[a][b][v] + bv;
-        const size_t o = (size_t)row * N + col;
-        if (e.residual) r += res[a][b][v];
-        if (e.out_f32) reinterpret_cast<float *>(e.y)[o] = r;
-        else reinterpret_cast<bf16_t *>(e.y)[o] = f2bf(r);
-        if (e.y2) e.y2[o] = f2bf(r);
-        if (e.hooks) {
-          const size_t hrow = ((size_t)(row / e.hook_q) * e.hook_qmax + row % e.hook_q) * 4;
-#pragma unroll
-          for (int g = 1; g < 4; ++g)
-            if (e.hook_mask >> g & 1) e.hooks[(hrow + g) * N + col] = f2bf(r);
-        }
-      }
-    }
 }
 
 // The bf16 kernel.  TM 32-row activation blocks x TN weight row blocks per wave, NW waves, ring
@@ -493,8 +530,23 @@ hipError_t run_ring(const GemmArgs &a, hipStream_t s, int split, int mode) {
   static_assert((size_t)2 * BM * LDK * sizeof(bf16_t) >= (size_t)NW * BM * 8, "arg-max partials fit the activation tile");
   const Epilogue e{(const bf16_t *)a.bias, a.residual, a.y, (bf16_t *)a.y2, (bf16_t *)a.hooks, a.am_val, a.am_idx,
                    a.hook_mask, a.hook_q, a.hook_qmax, a.am_stride, a.out_f32, a.res_f32, a.glu};
+  if (a.fused_norm) lds += (size_t)BM * sizeof(float);
+  if (lds > 64 * 1024) {  // more dynamic LDS than a kernel gets by default: raised once per device
+    static bool raised[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!raised[dev]) {
+      const int cap = 2 * BM * LDK * (int)sizeof(bf16_t) + BM * (int)sizeof(float);
+      hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_ring_kernel<TM, TN, R, OCC, NW, 1>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, cap);
+      if (err == hipSuccess)
+        err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_ring_kernel<TM, TN, R, OCC, NW, 0>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, cap);
+      if (err != hipSuccess) return err;
+      raised[dev] = true;
+    }
+  }
   if (a.fused_norm) {
-    lds += (size_t)BM * sizeof(float);
     gemm_ring_kernel<TM, TN, R, OCC, NW, 1><<<grid, block, lds, s>>>(
         (const bf16_t *)a.x, (const uint4 *)a.w, e, a.M, a.N, a.K, p.tiles_m, p.tiles_n, p.split_k, p.kt_per_split,
         partial, tickets, a.norm_eps, ssq_part);
@@ -507,7 +559,7 @@ hipError_t run_ring(const GemmArgs &a, hipStream_t s, int split, int mode) {
 }
 
 // Tile configurations: rows per workgroup TM*32, columns NW*32 (one 32-column block per wave).
-//   id  TM  ring  wg/CU  waves
+//   id  TM  ring  wg/CU  waves      (11-14: tall tiles for wide layers, see pick_large)
 hipError_t dispatch(int tile, const GemmArgs &a, hipStream_t s, int split, int mode) {
   switch (tile) {
     case 1: return run_ring<1, 1, 4, 4, 4>(a, s, split, mode);
@@ -520,11 +572,15 @@ hipError_t dispatch(int tile, const GemmArgs &a, hipStream_t s, int split, int m
     case 8: return run_ring<4, 1, 3, 1, 8>(a, s, split, mode);
     case 9: return run_ring<5, 1, 3, 1, 8>(a, s, split, mode);
     case 10: return run_ring<5, 1, 2, 1, 8>(a, s, split, mode);
+    case 11: return run_ring<10, 1, 2, 1, 8>(a, s, split, mode);
+    case 12: return run_ring<8, 1, 2, 1, 8>(a, s, split, mode);
+    case 13: return run_ring<7, 1, 2, 1, 8>(a, s, split, mode);
+    case 14: return run_ring<6, 1, 3, 1, 8>(a, s, split, mode);
     default: return hipErrorInvalidValue;
   }
 }
-constexpr int N_TILES = 10;
-constexpr int TILE_TM[N_TILES + 1] = {0, 1, 2, 3, 4, 5, 2, 3, 4, 5, 5};
+constexpr int N_TILES = 14, N_MODEL_TILES = 10;
+constexpr int TILE_TM[N_TILES + 1] = {0, 1, 2, 3, 4, 5, 2, 3, 4, 5, 5, 10, 8, 7, 6};
 
 // Heuristic choice (used when nothing was measured for the shape).  What the sweeps on MI355X
 // showed: a compute unit draws at most ~20-40 B/clk from L2, so both the weight re-reads of the
@@ -548,7 +604,7 @@ int pow2floor(int v) { int p = 1; while (p * 2 <= v) p *= 2; return p; }
 // layers at 384 ... 1792 rows, the 14B layers at 448 ... 896 rows and the two LM heads.  Over those the
 // model's choice is within 0.5 % of the best measured configuration on average (6.7 % worst).
 double model_us(int M, int N, int K, int tile, int split) {
-  static const double factor[N_TILES + 1] = {0, 1.0, 1.022, 1.005, 1.039, 1.121, 1.0, 0.947, 0.887, 0.938, 1.278};
+  static const double factor[N_MODEL_TILES + 1] = {0, 1.0, 1.022, 1.005, 1.039, 1.121, 1.0, 0.947, 0.887, 0.938, 1.278};
   const int BM = TILE_TM[tile] * 32, BN = tile >= 6 ? 256 : 128;
   const double tiles = (double)((M + BM - 1) / BM) * ((N + BN - 1) / BN) * split;
   const double per_cu = std::ceil(tiles / 256.0), ks = (double)K / split;
@@ -569,7 +625,7 @@ GemmConfig pick_large(int M, int N, int K, size_t ws_bytes, int fixed_split) {
   for (int split = 1; split <= 4; split *= 2) {
     if (fixed_split > 0 && split != fixed_split) continue;
     if (split > 1 && KT / split < 8) continue;
-    for (int tile = 2; tile <= N_TILES; ++tile) {
+    for (int tile = 2; tile <= N_MODEL_TILES; ++tile) {
       if (tile == 6) continue;  // 64 x 256: never competitive at this many rows
       if (split > 1) {
         const Plan p = make_plan(M, N, K, TILE_TM[tile] * 32, tile >= 6 ? 256 : 128, split);
@@ -578,6 +634,24 @@ GemmConfig pick_large(int M, int N, int K, size_t ws_bytes, int fixed_split) {
       const double us = model_us(M, N, K, tile, split);
       if (best.tile == 0 || us < best_us) { best = {tile, split}; best_us = us; }
     }
+  }
+  // Wide layers (gate/up, LM heads): where the model lands on an unsplit 256-column tile, a taller tile of
+  // the same width (192 ... 320 rows: the weights pass through fewer M-tiles) is 4-18 % faster in every
+  // sweep, provided it still gives ~200 workgroups and divides M with little padding.  Among those the
+  // one with the least work per compute unit is taken: rounds of 256 workgroups x (rows per workgroup + 32
+  // for what a workgroup costs besides its rows), weighted by the padded share of its rows -- the order the
+  // sweeps show.
+  if (best.split == 1 && best.tile >= 7 && best.tile <= N_MODEL_TILES) {
+    int tall = 0;
+    double tall_cost = 0;
+    for (int tile = N_MODEL_TILES + 1; tile <= N_TILES; ++tile) {  // 320, 256, 224, 192 rows
+      const int bm = TILE_TM[tile] * 32, tiles_m = (M + bm - 1) / bm, pad = tiles_m * bm - M;
+      const long wgs = (long)tiles_m * ((N + 255) / 256);
+      if (wgs < 200 || pad * 100 > 8 * M) continue;
+      const double cost = (double)((wgs + 255) / 256) * (bm + 32) * (M + pad) / M;
+      if (tall == 0 || cost < tall_cost) { tall = tile; tall_cost = cost; }
+    }
+    if (tall) best.tile = tall;
   }
   return best;
 }

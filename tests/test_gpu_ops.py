@@ -125,6 +125,39 @@ def test_linear_bf16_every_tile_and_split_gives_the_same_bits(M, N, K):
         eng.sf_tune_linear(0, 0)
 
 
+def test_linear_bf16_epilogues_of_every_tile_agree():
+    """Bias + residual (the output aliasing the residual) and the fused SwiGLU gate go through every tile
+    configuration, the tall ones included (their waves hold more than five 32x32 tiles and take the residual
+    in groups): all must leave the same bits, and those must match the oracle."""
+    M, N, K, F = 650, 392, 512, 224
+    g = synth.rng(23, M + N)
+    x = synth.to_bf16_values(g.standard_normal((M, K), dtype=np.float32))
+    w = synth.to_bf16_values(g.standard_normal((N, K), dtype=np.float32) * 0.05)
+    wgu = synth.to_bf16_values(g.standard_normal((2 * F, K), dtype=np.float32) * 0.05)
+    bias = synth.to_bf16_values(g.standard_normal(N, dtype=np.float32))
+    res = synth.to_bf16_values(g.standard_normal((M, N), dtype=np.float32))
+    eng = engine_only(shape_for("bf16", 2, 2, 64), 1, 64, 1)
+    xd, wd, bd, wgud = dev(x, "bf16"), dev(w, "bf16"), dev(bias, "bf16"), dev(wgu, "bf16")
+    packed = eng.sf_pack_weight(wd)
+    ref = sfo.linear(x, w, bias) + res
+    gu = sfo.linear(x, wgu)
+    ref_glu = gu[:, :F] / (1.0 + np.exp(-gu[:, :F])) * gu[:, F:]
+    try:
+        first = first_glu = None
+        for tile in range(1, sfb.lib().sf_linear_num_tiles() + 1):
+            eng.sf_tune_linear(tile, 1)
+            r = dev(res, "bf16")
+            eng.sf_op_linear(xd, None, bias=bd, residual=r, y=r, packed=(packed, N))
+            a = eng.sf_op_linear_swiglu(xd, wgud)
+            torch.cuda.synchronize()
+            assert rel_err(to_np(r), ref) < BF16_TOL and rel_err(to_np(a), ref_glu) < BF16_TOL, tile
+            if first is None:
+                first, first_glu = r.clone(), a.clone()
+            assert torch.equal(r, first) and torch.equal(a, first_glu), tile
+    finally:
+        eng.sf_tune_linear(0, 0)
+
+
 @pytest.mark.parametrize("M,N,K", [(160, 392, 2048), (77, 264, 200), (333, 520, 1792), (5, 128, 4096)])
 def test_rmsnorm_linear_fused(M, N, K):
     """The decoder's norm + linear pair as one kernel: against the oracle's RMSNorm followed by its
