@@ -603,7 +603,7 @@ int pow2floor(int v) { int p = 1; while (p * 2 <= v) p *= 2; return p; }
 // sweeps of all tiles x splits {1,2,4} (medians of interleaved repeats) of 30 shapes on MI355X: the 8B
 // layers at 384 ... 1792 rows, the 14B layers at 448 ... 896 rows and the two LM heads.  Over those the
 // model's choice is within 0.5 % of the best measured configuration on average (6.7 % worst).
-double model_us(int M, int N, int K, int tile, int split) {
+double model_us(int M, int N, int K, int tile, int split, bool fused_norm) {
   static const double factor[N_MODEL_TILES + 1] = {0, 1.0, 1.022, 1.005, 1.039, 1.121, 1.0, 0.947, 0.887, 0.938, 1.278};
   const int BM = TILE_TM[tile] * 32, BN = tile >= 6 ? 256 : 128;
   const double tiles = (double)((M + BM - 1) / BM) * ((N + BN - 1) / BN) * split;
@@ -613,12 +613,14 @@ double model_us(int M, int N, int K, int tile, int split) {
   const double t_hbm = (double)N * K * 2.0 / 4.7e12;
   const double t = std::max({t_mem, t_mma, t_hbm}) + 0.86 * std::min(t_mem, t_mma);
   const double t_split = split > 1 ? 8.1 + (double)M * N * 4.0 * split / 1.08e12 * 1e6 : 0.0;
-  return (t * 1e6 + 8.4 + t_split) * factor[tile];
+  // the 160 x 128 tile pays 16-28 % for the fused norm's row statistics (five chunks per staging thread and
+  // slice), every other tile 0-8 %
+  return (t * 1e6 + 8.4 + t_split) * factor[tile] * (fused_norm && tile == 5 ? 1.2 : 1.0);
 }
 
-GemmConfig pick(int M, int N, int K, size_t ws_bytes, int fixed_split);
+GemmConfig pick(int M, int N, int K, size_t ws_bytes, int fixed_split, bool fused_norm);
 
-GemmConfig pick_large(int M, int N, int K, size_t ws_bytes, int fixed_split) {
+GemmConfig pick_large(int M, int N, int K, size_t ws_bytes, int fixed_split, bool fused_norm) {
   const int KT = (K + BK - 1) / BK;
   GemmConfig best = {0, 0};
   double best_us = 0;
@@ -631,7 +633,7 @@ GemmConfig pick_large(int M, int N, int K, size_t ws_bytes, int fixed_split) {
         const Plan p = make_plan(M, N, K, TILE_TM[tile] * 32, tile >= 6 ? 256 : 128, split);
         if (!plan_fits(p, TILE_TM[tile] * 32, (const void *)1, ws_bytes)) continue;
       }
-      const double us = model_us(M, N, K, tile, split);
+      const double us = model_us(M, N, K, tile, split, fused_norm);
       if (best.tile == 0 || us < best_us) { best = {tile, split}; best_us = us; }
     }
   }
@@ -656,9 +658,9 @@ GemmConfig pick_large(int M, int N, int K, size_t ws_bytes, int fixed_split) {
   return best;
 }
 
-GemmConfig pick(int M, int N, int K, size_t ws_bytes, int fixed_split) {
+GemmConfig pick(int M, int N, int K, size_t ws_bytes, int fixed_split, bool fused_norm) {
   if (M >= 384 && (fixed_split <= 0 || fixed_split == 1 || fixed_split == 2 || fixed_split == 4)) {
-    const GemmConfig c = pick_large(M, N, K, ws_bytes, fixed_split);
+    const GemmConfig c = pick_large(M, N, K, ws_bytes, fixed_split, fused_norm);
     if (c.tile > 0) return c;
   }
   const int KT = (K + BK - 1) / BK;
@@ -765,11 +767,11 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
 int gemm_num_tiles() { return N_TILES; }
 int gemm_tile_rows(int tile) { return tile >= 1 && tile <= N_TILES ? TILE_TM[tile] * 32 : 0; }
 
-GemmConfig gemm_heuristic(int M, int plan_M, int N, int K, size_t ws_bytes) {
+GemmConfig gemm_heuristic(int M, int plan_M, int N, int K, size_t ws_bytes, bool fused_norm) {
   // The split factor is decided for plan_M rows and then kept for any M, so a row's result does
   // not depend on how many other rows share the launch; the tile follows the actual M.
-  const int split = pick(std::max(plan_M, M), N, K, ws_bytes, 0).split;
-  return pick(M, N, K, ws_bytes, split);
+  const int split = pick(std::max(plan_M, M), N, K, ws_bytes, 0, fused_norm).split;
+  return pick(M, N, K, ws_bytes, split, fused_norm);
 }
 
 bool gemm_config_fits(const GemmConfig &c, const GemmArgs &a) {
@@ -798,9 +800,9 @@ hipError_t launch_pack_weight(const void *w, void *packed, int N, int K, int glu
 hipError_t launch_gemm_bf16(const GemmArgs &a, hipStream_t s) {
   GemmConfig c = {a.tile, a.am_val ? 1 : a.split};  // arg-max partials: one workgroup owns a tile's whole K range
   if (c.tile <= 0 || c.split <= 0) {
-    const GemmConfig h = gemm_heuristic(a.M, a.plan_M > 0 ? a.plan_M : a.M, a.N, a.K, a.ws ? a.ws_bytes : 0);
+    const GemmConfig h = gemm_heuristic(a.M, a.plan_M > 0 ? a.plan_M : a.M, a.N, a.K, a.ws ? a.ws_bytes : 0, a.fused_norm != 0);
     if (c.split <= 0) c.split = h.split;
-    if (c.tile <= 0) c.tile = c.split == h.split ? h.tile : pick(a.M, a.N, a.K, a.ws ? a.ws_bytes : 0, c.split).tile;
+    if (c.tile <= 0) c.tile = c.split == h.split ? h.tile : pick(a.M, a.N, a.K, a.ws ? a.ws_bytes : 0, c.split, a.fused_norm != 0).tile;
   }
   return dispatch(c.tile, a, s, c.split, 0);
 }
