@@ -269,6 +269,10 @@ class Engine:
     def sf_op_attention(self, q, kc, vc, kv_len, n_q, mask, len_upper=None):
         """q [B,n_q,Hq,hd] device tensor; kc/vc tiled slabs; kv_len int32 device [B]."""
         B = q.shape[0]
+        slab = self.Hkv * self.cap * self.hd
+        if (tuple(q.shape) != (B, n_q, self.Hq, self.hd) or kv_len.numel() != B or kv_len.dtype != torch.int32
+                or kc.numel() < B * slab or vc.numel() < B * slab):
+            raise ValueError("sf_op_attention: q must be [B,n_q,Hq,hd], kv_len int32 [B], caches at least B slabs")
         if len_upper is None:
             len_upper = int(kv_len.max().item())
         need = self.lib.sf_attention_workspace_bytes(self.ctx, B, n_q, len_upper)
@@ -381,6 +385,11 @@ class Engine:
     def sf_op_rope_attention(self, qkv, kv_len, n_q, kc, vc, mask, len_upper=None):
         """Rotate + append + attend in one kernel (bf16).  qkv [B*n_q,(Hq+2Hkv)*hd]; returns [B,n_q,Hq,hd]."""
         B = kv_len.shape[0]
+        slab = self.Hkv * self.cap * self.hd
+        if (qkv.numel() != B * n_q * (self.Hq + 2 * self.Hkv) * self.hd or kv_len.dtype != torch.int32
+                or kc.numel() < B * slab or vc.numel() < B * slab):
+            raise ValueError("sf_op_rope_attention: qkv must be [B*n_q,(Hq+2Hkv)*hd], kv_len int32 [B], "
+                             "caches at least B slabs")
         if len_upper is None:
             len_upper = int(kv_len.max().item())
         need = self.lib.sf_rope_attention_workspace_bytes(self.ctx, B, n_q, len_upper)
