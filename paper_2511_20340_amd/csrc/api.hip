@@ -351,6 +351,9 @@ sf_status sf_bind(sf_ctx *c, const sf_target_weights *t, const sf_draft_weights 
   c->w_down.assign(t->w_down, t->w_down + L);
   c->has_draft = d != nullptr;
   if (d) c->dw = *d;
+  // function attributes of the tall linear tiles, set here so that the first launch (possibly under stream
+  // capture) has nothing left to set; best effort -- a launch repeats the call and reports its error
+  if (c->tc.dtype == SF_BF16) (void)gemm_prepare_device();
   c->bound = true;
   return SF_OK;
 }

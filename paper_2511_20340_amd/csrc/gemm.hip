@@ -512,6 +512,26 @@ bool plan_fits(const Plan &p, int BM, const void *ws, size_t ws_bytes) {
          p.ticket_bytes <= GEMM_TICKET_BYTES && ssq_bytes <= GEMM_SSQ_BYTES;
 }
 
+// A tile whose activation double buffer exceeds the 64 KiB of dynamic LDS a kernel gets by default has the
+// limit of both its kernels (with and without the fused norm) raised, once per device.
+template <int TM, int TN, int R, int OCC, int NW>
+hipError_t ensure_lds() {
+  constexpr int BM = TM * 32;
+  constexpr int cap = 2 * BM * LDK * (int)sizeof(bf16_t) + BM * (int)sizeof(float);
+  if (cap <= 64 * 1024) return hipSuccess;
+  static bool raised[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (raised[dev]) return hipSuccess;
+  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_ring_kernel<TM, TN, R, OCC, NW, 1>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, cap);
+  if (err == hipSuccess)
+    err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_ring_kernel<TM, TN, R, OCC, NW, 0>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, cap);
+  if (err == hipSuccess) raised[dev] = true;
+  return err;
+}
+
 // mode 0: launch; mode 1: only report whether (split) fits the workspace
 template <int TM, int TN, int R, int OCC, int NW>
 hipError_t run_ring(const GemmArgs &a, hipStream_t s, int split, int mode) {
@@ -531,20 +551,9 @@ hipError_t run_ring(const GemmArgs &a, hipStream_t s, int split, int mode) {
   const Epilogue e{(const bf16_t *)a.bias, a.residual, a.y, (bf16_t *)a.y2, (bf16_t *)a.hooks, a.am_val, a.am_idx,
                    a.hook_mask, a.hook_q, a.hook_qmax, a.am_stride, a.out_f32, a.res_f32, a.glu};
   if (a.fused_norm) lds += (size_t)BM * sizeof(float);
-  if (lds > 64 * 1024) {  // more dynamic LDS than a kernel gets by default: raised once per device
-    static bool raised[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    if (!raised[dev]) {
-      const int cap = 2 * BM * LDK * (int)sizeof(bf16_t) + BM * (int)sizeof(float);
-      hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_ring_kernel<TM, TN, R, OCC, NW, 1>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, cap);
-      if (err == hipSuccess)
-        err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_ring_kernel<TM, TN, R, OCC, NW, 0>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, cap);
-      if (err != hipSuccess) return err;
-      raised[dev] = true;
-    }
+  if (lds > 64 * 1024) {
+    const hipError_t err = ensure_lds<TM, TN, R, OCC, NW>();
+    if (err != hipSuccess) return err;
   }
   if (a.fused_norm) {
     gemm_ring_kernel<TM, TN, R, OCC, NW, 1><<<grid, block, lds, s>>>(
@@ -763,6 +772,16 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
 }
 
 }  // namespace
+
+// Called when weights are bound (outside any stream capture): the attribute calls of the tall tiles are
+// then out of the way of the first launch.
+hipError_t gemm_prepare_device() {
+  hipError_t err = ensure_lds<10, 1, 2, 1, 8>();
+  if (err == hipSuccess) err = ensure_lds<8, 1, 2, 1, 8>();
+  if (err == hipSuccess) err = ensure_lds<7, 1, 2, 1, 8>();
+  if (err == hipSuccess) err = ensure_lds<6, 1, 3, 1, 8>();
+  return err;
+}
 
 int gemm_num_tiles() { return N_TILES; }
 int gemm_tile_rows(int tile) { return tile >= 1 && tile <= N_TILES ? TILE_TM[tile] * 32 : 0; }

@@ -128,6 +128,7 @@ constexpr size_t GEMM_TICKET_BYTES = 64 * 1024;
 constexpr size_t GEMM_PARTIAL_BYTES = 96u * 1024 * 1024;
 constexpr size_t GEMM_SSQ_BYTES = 1024 * 1024;  // split-K: per-split row sums of squares of the fused norm
 size_t gemm_workspace_bytes(int M_max);
+hipError_t gemm_prepare_device();
 int gemm_num_tiles();
 int gemm_tile_rows(int tile);
 GemmConfig gemm_heuristic(int M, int plan_M, int N, int K, size_t ws_bytes, bool fused_norm = false);
