@@ -59,7 +59,9 @@ def test_attention_full_shape_sampled_sequences(name, B, Hq, Hkv, hd, lo, hi, nq
 @pytest.mark.parametrize("M,N,K,glu", [
     (160, 3072, 2048, False), (160, 2048, 8192, False), (160, 32000, 2048, False), (160, 16384, 2048, True),
     (32, 2048, 8192, False), (320, 6144, 4096, False), (320, 4096, 14336, False), (320, 28672, 4096, True),
-    (1280, 28672, 4096, True), (640, 5120, 13824, False)])
+    (1280, 28672, 4096, True), (640, 5120, 13824, False),
+    # wide layers that take the tall tiles (320 / 256 / 224 / 192 rows per workgroup)
+    (640, 27648, 5120, True), (1024, 28672, 4096, True), (896, 27648, 5120, False), (768, 28672, 4096, False)])
 def test_linear_full_shape_sampled_outputs(M, N, K, glu):
     x = device_normal((M, K), 5)
     w = (device_normal((N, K), 6, torch.float32) * 0.02).to(torch.bfloat16)
@@ -351,6 +353,43 @@ def test_real_width_two_layer_steps_teacher_forced(index, k, fixed_prefix):
 
 
 # ---- a verify pass over more attention workgroups than the chip holds: sequences ranked by length ---------
+def test_batch128_step_bits_do_not_depend_on_the_linear_tiles():
+    """The 14B-shaped model at one layer, the benchmark's batch (128 sequences, k = 4: 640 rows, where the
+    wide layers run on the tall tiles): drafts, target choices, logits-free hooks and the appended K/V must be
+    bit-identical when every linear layer is forced onto the 160-row and the 128-row tiles instead."""
+    wl = synth.WORKLOADS[4]
+    m = wl.model.scaled(n_layers=1)
+    B, k = 128, 4
+    g = synth.rng(wl.seed, 991)
+    lens = g.integers(40, 97, B).astype(np.int32)
+    cap = synth.kv_capacity(int(lens.max()), 2, k)
+    eng = Engine(m.cfg(), B, cap, k)
+    eng.bind(*synth.device_weights(m, k, wl.seed))
+    for which in ("tk", "tv", "dk", "dv"):
+        buf = getattr(eng, which)
+        buf.copy_(device_normal((buf.numel(),), 300 + ord(which[0]) + ord(which[1])))
+    hooks0 = device_normal(tuple(eng.hooks.shape), 11)
+    results = []
+    try:
+        for tile in (0, 9, 4):
+            eng.sf_tune_linear(tile, 0)
+            eng.hooks.copy_(hooks0)
+            eng.set_state(kv_len=lens, pending=g.integers(0, m.vocab, B).astype(np.int32) if not results else pending,
+                          n_new=np.ones(B, np.int32))
+            if not results:
+                pending = eng.pending.cpu().numpy().copy()
+            draft = eng.sf_draft_step(k)
+            _, ids = eng.sf_verify_step(k, draft, logits=False)
+            torch.cuda.synchronize()
+            results.append((draft.clone(), ids.clone(), eng.hooks.clone(), eng.tk.clone(), eng.dv.clone()))
+    finally:
+        eng.sf_tune_linear(0, 0)
+    for other in results[1:]:
+        for a, b in zip(results[0], other):
+            assert torch.equal(a, b)
+    assert (results[0][1] >= 0).all() and (results[0][1] < m.vocab).all()
+
+
 def test_verify_with_length_ranked_attention_three_sequences_against_oracle():
     """272 ragged sequences x 2 kv heads = 544 attention workgroups: above 512 the verify pass starts the
     longest sequences first (a device-side ranking).  The longest, the shortest and a middle sequence,
