@@ -315,7 +315,7 @@ __device__ __forceinline__ void gemm_finish(f32x16 (&acc)[TM][TN], const Epilogu
 // The bf16 kernel.  TM 32-row activation blocks x TN weight row blocks per wave, NW waves, ring
 // depth R.  Slot indices are compile-time after unrolling by R; the loop runs whole rounds of R
 // slices, and slices past the workgroup's K range contribute zeros.
-template <int TM, int TN, int R, int OCC, int NW, int NORM>
+template <int TM, int TN, int R, int OCC, int NW, int NORM, int PIPE = 0>
 __global__ __launch_bounds__(64 * NW, OCC) void gemm_ring_kernel(const bf16_t *__restrict__ A,
                                                         const uint4 *__restrict__ Wp, const Epilogue e, int M,
                                                         int N, int K, int tiles_m, int tiles_n, int split_k,
@@ -417,6 +417,43 @@ __global__ __launch_bounds__(64 * NW, OCC) void gemm_ring_kernel(const bf16_t *_
     for (int r = 0; r < R; ++r) {
       const int kt = base + r, buf = (kt - kt0) & 1;
       const bf16_t *pa = sA + (buf * BM + ln) * LDK + lh * 8;
+      if constexpr (PIPE) {
+        // Issue order pinned by hand: the slot's next activation chunk is requested first; the activation
+        // fragments of k-step s + 1 are requested before the products of k-step s are issued, so that the LDS
+        // latency of all but the slice's first k-step runs under MFMAs; each k-step's weight registers are
+        // refilled as soon as its products are issued.
+        bf16x8 fa[2][TM];
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+          fa[0][a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pa + a * 32 * LDK));
+        aload(ra[r], kt + R);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          if (s + 1 < 4) {
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+              fa[(s + 1) & 1][a] =
+                  __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pa + a * 32 * LDK + (s + 1) * 16));
+          }
+          if (s == 1) astore(buf ^ 1, ra[(r + 1) % R], kt + 1);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1][a], __builtin_bit_cast(bf16x8, w[r][s][b]),
+                                                                  acc[a][b], 0, 0, 0);
+#pragma unroll
+          for (int b = 0; b < TN; ++b) {
+            const int kstep = min((kt + R) * 4 + s, k_steps - 1), nb = min(nb0 + b, n_blocks - 1);
+            w[r][s][b] = Wp[((size_t)nb * k_steps + kstep) * 64 + lane];
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();
+        continue;
+      }
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
 #pragma unroll
@@ -514,7 +551,7 @@ bool plan_fits(const Plan &p, int BM, const void *ws, size_t ws_bytes) {
 
 // A tile whose activation double buffer exceeds the 64 KiB of dynamic LDS a kernel gets by default has the
 // limit of both its kernels (with and without the fused norm) raised, once per device.
-template <int TM, int TN, int R, int OCC, int NW>
+template <int TM, int TN, int R, int OCC, int NW, int PIPE = 0>
 hipError_t ensure_lds() {
   constexpr int BM = TM * 32;
   constexpr int cap = 2 * BM * LDK * (int)sizeof(bf16_t) + BM * (int)sizeof(float);
@@ -523,17 +560,17 @@ hipError_t ensure_lds() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
   if (raised[dev]) return hipSuccess;
-  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_ring_kernel<TM, TN, R, OCC, NW, 1>),
+  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_ring_kernel<TM, TN, R, OCC, NW, 1, PIPE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, cap);
   if (err == hipSuccess)
-    err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_ring_kernel<TM, TN, R, OCC, NW, 0>),
+    err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_ring_kernel<TM, TN, R, OCC, NW, 0, PIPE>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, cap);
   if (err == hipSuccess) raised[dev] = true;
   return err;
 }
 
 // mode 0: launch; mode 1: only report whether (split) fits the workspace
-template <int TM, int TN, int R, int OCC, int NW>
+template <int TM, int TN, int R, int OCC, int NW, int PIPE = 0>
 hipError_t run_ring(const GemmArgs &a, hipStream_t s, int split, int mode) {
   constexpr int BM = TM * 32, BN = NW * TN * 32;
   const Plan p = make_plan(a.M, a.N, a.K, BM, BN, split);
@@ -552,15 +589,15 @@ hipError_t run_ring(const GemmArgs &a, hipStream_t s, int split, int mode) {
                    a.hook_mask, a.hook_q, a.hook_qmax, a.am_stride, a.out_f32, a.res_f32, a.glu};
   if (a.fused_norm) lds += (size_t)BM * sizeof(float);
   if (lds > 64 * 1024) {
-    const hipError_t err = ensure_lds<TM, TN, R, OCC, NW>();
+    const hipError_t err = ensure_lds<TM, TN, R, OCC, NW, PIPE>();
     if (err != hipSuccess) return err;
   }
   if (a.fused_norm) {
-    gemm_ring_kernel<TM, TN, R, OCC, NW, 1><<<grid, block, lds, s>>>(
+    gemm_ring_kernel<TM, TN, R, OCC, NW, 1, PIPE><<<grid, block, lds, s>>>(
         (const bf16_t *)a.x, (const uint4 *)a.w, e, a.M, a.N, a.K, p.tiles_m, p.tiles_n, p.split_k, p.kt_per_split,
         partial, tickets, a.norm_eps, ssq_part);
   } else {
-    gemm_ring_kernel<TM, TN, R, OCC, NW, 0><<<grid, block, lds, s>>>(
+    gemm_ring_kernel<TM, TN, R, OCC, NW, 0, PIPE><<<grid, block, lds, s>>>(
         (const bf16_t *)a.x, (const uint4 *)a.w, e, a.M, a.N, a.K, p.tiles_m, p.tiles_n, p.split_k, p.kt_per_split,
         partial, tickets, 0.f, nullptr);
   }
@@ -569,18 +606,25 @@ hipError_t run_ring(const GemmArgs &a, hipStream_t s, int split, int mode) {
 
 // Tile configurations: rows per workgroup TM*32, columns NW*32 (one 32-column block per wave).
 //   id  TM  ring  wg/CU  waves      (11-14: tall tiles for wide layers, see pick_large)
+// A sixth template argument of 1 selects the hand-pinned issue order of the slice (same arithmetic, same
+// bits).  Measured against the compiler's order on 27 shapes x splits {1, 2, 4}: 2-12 % faster on the 96-row
+// tiles and the 128-row tiles, up to 17 % on the 64 x 256 tile, 9-60 % on the two-slot 160 x 256 tile (which
+// then beats the three-slot one in the compiler's order by 1-4 % everywhere; pinned, the three-slot one is
+// 1-5 % slower than unpinned); under the pinned order two ring slots beat three by 1-5 % on the 128-row
+// tiles, four slots stay best on the 96-row ones.  The 192-row tile is faster in the compiler's order, and
+// the taller tiles and the 160 x 128 tile have no registers left for the pinned one.
 hipError_t dispatch(int tile, const GemmArgs &a, hipStream_t s, int split, int mode) {
   switch (tile) {
     case 1: return run_ring<1, 1, 4, 4, 4>(a, s, split, mode);
     case 2: return run_ring<2, 1, 4, 3, 4>(a, s, split, mode);
-    case 3: return run_ring<3, 1, 4, 2, 4>(a, s, split, mode);
-    case 4: return run_ring<4, 1, 3, 2, 4>(a, s, split, mode);
+    case 3: return run_ring<3, 1, 4, 2, 4, 1>(a, s, split, mode);
+    case 4: return run_ring<4, 1, 2, 2, 4, 1>(a, s, split, mode);
     case 5: return run_ring<5, 1, 3, 2, 4>(a, s, split, mode);
-    case 6: return run_ring<2, 1, 4, 1, 8>(a, s, split, mode);
-    case 7: return run_ring<3, 1, 4, 1, 8>(a, s, split, mode);
-    case 8: return run_ring<4, 1, 3, 1, 8>(a, s, split, mode);
+    case 6: return run_ring<2, 1, 2, 1, 8, 1>(a, s, split, mode);
+    case 7: return run_ring<3, 1, 4, 1, 8, 1>(a, s, split, mode);
+    case 8: return run_ring<4, 1, 2, 1, 8, 1>(a, s, split, mode);
     case 9: return run_ring<5, 1, 3, 1, 8>(a, s, split, mode);
-    case 10: return run_ring<5, 1, 2, 1, 8>(a, s, split, mode);
+    case 10: return run_ring<5, 1, 2, 1, 8, 1>(a, s, split, mode);
     case 11: return run_ring<10, 1, 2, 1, 8>(a, s, split, mode);
     case 12: return run_ring<8, 1, 2, 1, 8>(a, s, split, mode);
     case 13: return run_ring<7, 1, 2, 1, 8>(a, s, split, mode);
@@ -610,10 +654,12 @@ int pow2floor(int v) { int p = 1; while (p * 2 <= v) p *= 2; return p; }
 // partial tiles (M * N * 4 * split bytes) at ~1.1 TB/s.  The constants and the per-tile factors were
 // searched for the smallest regret of the choice, with the model's own error held at 13 % rms, over
 // sweeps of all tiles x splits {1,2,4} (medians of interleaved repeats) of 30 shapes on MI355X: the 8B
-// layers at 384 ... 1792 rows, the 14B layers at 448 ... 896 rows and the two LM heads.  Over those the
-// model's choice is within 0.5 % of the best measured configuration on average (6.7 % worst).
+// layers at 384 ... 1792 rows, the 14B layers at 448 ... 896 rows and the two LM heads; the factors of the
+// tiles whose issue order was pinned later (7, 8, 10) were lowered by what the pinning gained in a repeat of
+// the same sweeps.  Over the 32 shapes of that repeat the choice (this model, then the tall-tile rule) is
+// the fastest measured configuration of every shape.
 double model_us(int M, int N, int K, int tile, int split, bool fused_norm) {
-  static const double factor[N_MODEL_TILES + 1] = {0, 1.0, 1.022, 1.005, 1.039, 1.121, 1.0, 0.947, 0.887, 0.938, 1.278};
+  static const double factor[N_MODEL_TILES + 1] = {0, 1.0, 1.022, 1.005, 1.015, 1.121, 1.0, 0.889, 0.842, 0.938, 0.910};
   const int BM = TILE_TM[tile] * 32, BN = tile >= 6 ? 256 : 128;
   const double tiles = (double)((M + BM - 1) / BM) * ((N + BN - 1) / BN) * split;
   const double per_cu = std::ceil(tiles / 256.0), ks = (double)K / split;
@@ -682,7 +728,8 @@ GemmConfig pick(int M, int N, int K, size_t ws_bytes, int fixed_split, bool fuse
   };
   auto with_waves = [&](int tm, int split) {  // 8-wave workgroups when the grid stays full
     const int tiles_m = (M + tm * 32 - 1) / (tm * 32);
-    return (tm >= 2 && split == 1 && tiles_m * cols8 >= WG_FULL) ? tm + 4 : tm;
+    if (!(tm >= 2 && split == 1 && tiles_m * cols8 >= WG_FULL)) return tm;
+    return tm == 5 ? 10 : tm + 4;  // of the two 160 x 256 tiles the two-slot one is 1-4 % faster at every shape measured
   };
   auto fits = [&](int tm, int split) {
     if (split == 1) return true;
