@@ -611,15 +611,17 @@ hipError_t run_ring(const GemmArgs &a, hipStream_t s, int split, int mode) {
 // tiles and the 128-row tiles, up to 17 % on the 64 x 256 tile, 9-60 % on the two-slot 160 x 256 tile (which
 // then beats the three-slot one in the compiler's order by 1-4 % everywhere; pinned, the three-slot one is
 // 1-5 % slower than unpinned); under the pinned order two ring slots beat three by 1-5 % on the 128-row
-// tiles, four slots stay best on the 96-row ones.  The 192-row tile is faster in the compiler's order, and
-// the taller tiles and the 160 x 128 tile have no registers left for the pinned one.
+// tiles, four slots stay best on the 96-row ones; the 160 x 128 tile fits the pinned order with two slots and
+// gains 5-10 % (15-22 % with the fused norm, whose extra cost drops to the 1-9 % of the other tiles).  The
+// 32- and 64-row tiles move by +-3 % either way and stay as they were, the 192-row tile is faster in the
+// compiler's order, and the taller tiles have no registers left for the pinned one.
 hipError_t dispatch(int tile, const GemmArgs &a, hipStream_t s, int split, int mode) {
   switch (tile) {
     case 1: return run_ring<1, 1, 4, 4, 4>(a, s, split, mode);
     case 2: return run_ring<2, 1, 4, 3, 4>(a, s, split, mode);
     case 3: return run_ring<3, 1, 4, 2, 4, 1>(a, s, split, mode);
     case 4: return run_ring<4, 1, 2, 2, 4, 1>(a, s, split, mode);
-    case 5: return run_ring<5, 1, 3, 2, 4>(a, s, split, mode);
+    case 5: return run_ring<5, 1, 2, 2, 4, 1>(a, s, split, mode);
     case 6: return run_ring<2, 1, 2, 1, 8, 1>(a, s, split, mode);
     case 7: return run_ring<3, 1, 4, 1, 8, 1>(a, s, split, mode);
     case 8: return run_ring<4, 1, 2, 1, 8, 1>(a, s, split, mode);
@@ -655,11 +657,11 @@ int pow2floor(int v) { int p = 1; while (p * 2 <= v) p *= 2; return p; }
 // searched for the smallest regret of the choice, with the model's own error held at 13 % rms, over
 // sweeps of all tiles x splits {1,2,4} (medians of interleaved repeats) of 30 shapes on MI355X: the 8B
 // layers at 384 ... 1792 rows, the 14B layers at 448 ... 896 rows and the two LM heads; the factors of the
-// tiles whose issue order was pinned later (7, 8, 10) were lowered by what the pinning gained in a repeat of
+// tiles whose issue order was pinned later (4, 5, 7, 8, 10) were lowered by what the pinning gained in a repeat of
 // the same sweeps.  Over the 32 shapes of that repeat the choice (this model, then the tall-tile rule) is
 // the fastest measured configuration of every shape.
-double model_us(int M, int N, int K, int tile, int split, bool fused_norm) {
-  static const double factor[N_MODEL_TILES + 1] = {0, 1.0, 1.022, 1.005, 1.015, 1.121, 1.0, 0.889, 0.842, 0.938, 0.910};
+double model_us(int M, int N, int K, int tile, int split) {
+  static const double factor[N_MODEL_TILES + 1] = {0, 1.0, 1.022, 1.005, 1.015, 1.080, 1.0, 0.889, 0.842, 0.938, 0.910};
   const int BM = TILE_TM[tile] * 32, BN = tile >= 6 ? 256 : 128;
   const double tiles = (double)((M + BM - 1) / BM) * ((N + BN - 1) / BN) * split;
   const double per_cu = std::ceil(tiles / 256.0), ks = (double)K / split;
@@ -668,14 +670,12 @@ double model_us(int M, int N, int K, int tile, int split, bool fused_norm) {
   const double t_hbm = (double)N * K * 2.0 / 4.7e12;
   const double t = std::max({t_mem, t_mma, t_hbm}) + 0.86 * std::min(t_mem, t_mma);
   const double t_split = split > 1 ? 8.1 + (double)M * N * 4.0 * split / 1.08e12 * 1e6 : 0.0;
-  // the 160 x 128 tile pays 16-28 % for the fused norm's row statistics (five chunks per staging thread and
-  // slice), every other tile 0-8 %
-  return (t * 1e6 + 8.4 + t_split) * factor[tile] * (fused_norm && tile == 5 ? 1.2 : 1.0);
+  return (t * 1e6 + 8.4 + t_split) * factor[tile];
 }
 
-GemmConfig pick(int M, int N, int K, size_t ws_bytes, int fixed_split, bool fused_norm);
+GemmConfig pick(int M, int N, int K, size_t ws_bytes, int fixed_split);
 
-GemmConfig pick_large(int M, int N, int K, size_t ws_bytes, int fixed_split, bool fused_norm) {
+GemmConfig pick_large(int M, int N, int K, size_t ws_bytes, int fixed_split) {
   const int KT = (K + BK - 1) / BK;
   GemmConfig best = {0, 0};
   double best_us = 0;
@@ -688,7 +688,7 @@ GemmConfig pick_large(int M, int N, int K, size_t ws_bytes, int fixed_split, boo
         const Plan p = make_plan(M, N, K, TILE_TM[tile] * 32, tile >= 6 ? 256 : 128, split);
         if (!plan_fits(p, TILE_TM[tile] * 32, (const void *)1, ws_bytes)) continue;
       }
-      const double us = model_us(M, N, K, tile, split, fused_norm);
+      const double us = model_us(M, N, K, tile, split);
       if (best.tile == 0 || us < best_us) { best = {tile, split}; best_us = us; }
     }
   }
@@ -713,9 +713,9 @@ GemmConfig pick_large(int M, int N, int K, size_t ws_bytes, int fixed_split, boo
   return best;
 }
 
-GemmConfig pick(int M, int N, int K, size_t ws_bytes, int fixed_split, bool fused_norm) {
+GemmConfig pick(int M, int N, int K, size_t ws_bytes, int fixed_split) {
   if (M >= 384 && (fixed_split <= 0 || fixed_split == 1 || fixed_split == 2 || fixed_split == 4)) {
-    const GemmConfig c = pick_large(M, N, K, ws_bytes, fixed_split, fused_norm);
+    const GemmConfig c = pick_large(M, N, K, ws_bytes, fixed_split);
     if (c.tile > 0) return c;
   }
   const int KT = (K + BK - 1) / BK;
@@ -833,11 +833,11 @@ hipError_t gemm_prepare_device() {
 int gemm_num_tiles() { return N_TILES; }
 int gemm_tile_rows(int tile) { return tile >= 1 && tile <= N_TILES ? TILE_TM[tile] * 32 : 0; }
 
-GemmConfig gemm_heuristic(int M, int plan_M, int N, int K, size_t ws_bytes, bool fused_norm) {
+GemmConfig gemm_heuristic(int M, int plan_M, int N, int K, size_t ws_bytes) {
   // The split factor is decided for plan_M rows and then kept for any M, so a row's result does
   // not depend on how many other rows share the launch; the tile follows the actual M.
-  const int split = pick(std::max(plan_M, M), N, K, ws_bytes, 0, fused_norm).split;
-  return pick(M, N, K, ws_bytes, split, fused_norm);
+  const int split = pick(std::max(plan_M, M), N, K, ws_bytes, 0).split;
+  return pick(M, N, K, ws_bytes, split);
 }
 
 bool gemm_config_fits(const GemmConfig &c, const GemmArgs &a) {
@@ -866,9 +866,9 @@ hipError_t launch_pack_weight(const void *w, void *packed, int N, int K, int glu
 hipError_t launch_gemm_bf16(const GemmArgs &a, hipStream_t s) {
   GemmConfig c = {a.tile, a.am_val ? 1 : a.split};  // arg-max partials: one workgroup owns a tile's whole K range
   if (c.tile <= 0 || c.split <= 0) {
-    const GemmConfig h = gemm_heuristic(a.M, a.plan_M > 0 ? a.plan_M : a.M, a.N, a.K, a.ws ? a.ws_bytes : 0, a.fused_norm != 0);
+    const GemmConfig h = gemm_heuristic(a.M, a.plan_M > 0 ? a.plan_M : a.M, a.N, a.K, a.ws ? a.ws_bytes : 0);
     if (c.split <= 0) c.split = h.split;
-    if (c.tile <= 0) c.tile = c.split == h.split ? h.tile : pick(a.M, a.N, a.K, a.ws ? a.ws_bytes : 0, c.split, a.fused_norm != 0).tile;
+    if (c.tile <= 0) c.tile = c.split == h.split ? h.tile : pick(a.M, a.N, a.K, a.ws ? a.ws_bytes : 0, c.split).tile;
   }
   return dispatch(c.tile, a, s, c.split, 0);
 }

@@ -131,7 +131,7 @@ size_t gemm_workspace_bytes(int M_max);
 hipError_t gemm_prepare_device();
 int gemm_num_tiles();
 int gemm_tile_rows(int tile);
-GemmConfig gemm_heuristic(int M, int plan_M, int N, int K, size_t ws_bytes, bool fused_norm = false);
+GemmConfig gemm_heuristic(int M, int plan_M, int N, int K, size_t ws_bytes);
 bool gemm_config_fits(const GemmConfig &c, const GemmArgs &a);  // split-K partials fit a.ws?
 // bf16 weights are consumed in MFMA-operand-packed form (see gemm.hip); fp32 weights stay row-major
 size_t packed_weight_bytes(int N, int K, int dtype);

@@ -64,24 +64,24 @@ MEASURED_NEAR_BEST = {
     (512, 5120, 5120): {(3, 1)},
     (512, 5120, 13824): {(3, 1), (7, 2)},
     (512, 7168, 5120): {(4, 1)},
-    (512, 27648, 5120): {(12, 1)},
+    (512, 27648, 5120): {(8, 1), (12, 1)},
     (640, 5120, 5120): {(4, 1)},
     (640, 5120, 13824): {(8, 2)},
     (640, 5120, 20480): {(8, 2)},
-    (640, 7168, 5120): {(7, 1)},
-    (640, 27648, 5120): {(11, 1)},
-    (640, 152064, 5120): {(11, 1)},
+    (640, 7168, 5120): {(5, 1), (7, 1)},
+    (640, 27648, 5120): {(9, 1), (10, 1), (11, 1)},
+    (640, 152064, 5120): {(8, 1), (10, 1), (11, 1)},
     (768, 4096, 14336): {(3, 1), (7, 2)},
     (768, 6144, 4096): {(7, 1)},
     (768, 28672, 4096): {(14, 1)},
     (896, 27648, 5120): {(13, 1)},
     (896, 152064, 5120): {(8, 1), (13, 1), (14, 1)},
     (1024, 4096, 4096): {(4, 1)},
-    (1024, 4096, 14336): {(8, 2)},
+    (1024, 4096, 14336): {(4, 1), (8, 2)},
     (1024, 6144, 4096): {(8, 1)},
     (1024, 28672, 4096): {(12, 1)},
     (1280, 4096, 4096): {(7, 1)},
-    (1280, 4096, 14336): {(9, 2), (10, 2), (14, 2)},
+    (1280, 4096, 14336): {(7, 1), (9, 2), (10, 2)},
     (1280, 6144, 4096): {(8, 1)},
     (1280, 28672, 4096): {(11, 1)},
     (1280, 128256, 4096): {(11, 1), (12, 1)},
