@@ -27,7 +27,7 @@ constexpr float NEG_INF = -__builtin_huge_valf();
 // read back by the same workgroup after a barrier; workgroups that share (sequence, kv head) own
 // disjoint tiles, or (several row groups) write identical values.
 template <int HD, int FUSE>
-__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
+__global__ __launch_bounds__(256, HD == 64 ? 4 : 2) void attn_bf16_kernel(
     const bf16_t *__restrict__ Q, const uint4 *Kc, const uint4 *Vc,
     const int32_t *__restrict__ kv_len, bf16_t *__restrict__ O, float *__restrict__ part_o,
     float *__restrict__ part_ml, int n_q, int Hq, int Hkv, int cap, int mode, int chunk_tiles,
@@ -77,22 +77,56 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     constexpr int HALF = HD / 2;
     const size_t row_stride = (size_t)(Hq + 2 * Hkv) * HD;
     // the block's new rows that live in this workgroup's tiles: rotate K, append K and V
-    bf16_t *Kw = reinterpret_cast<bf16_t *>(const_cast<uint4 *>(Kc)) + seq_base * 8;
     bf16_t *Vw = reinterpret_cast<bf16_t *>(const_cast<uint4 *>(Vc)) + seq_base * 8;
-    for (int x = tid; x < n_q * HALF; x += 256) {
-      const int j = x / HALF, e = x % HALF;
+    // K: one thread per (new row, 8 features of the lower half): both halves of the rotation pairs leave as
+    // whole 16-byte units
+    for (int x = tid; x < n_q * (HALF / 8); x += 256) {
+      const int j = x / (HALF / 8), c8 = x % (HALF / 8);
       const int pos = len + j, tile = pos / TK, a_in = pos % TK;
       if (tile < t_begin || tile >= t_end) continue;
       const bf16_t *src = Q + ((size_t)b * n_q + j) * row_stride + (size_t)(Hq + g) * HD;
-      const float2 cs = table[((size_t)b * n_q + j) * HALF + e];
-      const float a = bf2f(src[e]), bb = bf2f(src[e + HALF]);
+      const uint4 lo4 = *reinterpret_cast<const uint4 *>(src + c8 * 8);
+      const uint4 hi4 = *reinterpret_cast<const uint4 *>(src + HALF + c8 * 8);
+      const unsigned lo[4] = {lo4.x, lo4.y, lo4.z, lo4.w}, hi[4] = {hi4.x, hi4.y, hi4.z, hi4.w};
+      const float2 *cs = table + ((size_t)b * n_q + j) * HALF + c8 * 8;
+      unsigned k0[4], k1[4];
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {  // two features per 32-bit word
+        float a0, a1, b0, b1;
+        rope_pair(bf2f((bf16_t)(lo[w] & 0xffffu)), bf2f((bf16_t)(hi[w] & 0xffffu)), cs[2 * w], a0, a1);
+        rope_pair(bf2f((bf16_t)(lo[w] >> 16)), bf2f((bf16_t)(hi[w] >> 16)), cs[2 * w + 1], b0, b1);
+        k0[w] = (unsigned)f2bf(a0) | ((unsigned)f2bf(b0) << 16);
+        k1[w] = (unsigned)f2bf(a1) | ((unsigned)f2bf(b1) << 16);
+      }
+      const uint4 o0 = make_uint4(k0[0], k0[1], k0[2], k0[3]), o1 = make_uint4(k1[0], k1[1], k1[2], k1[3]);
+      uint4 *Ku = const_cast<uint4 *>(Kc) + seq_base + (size_t)tile * TILE_U4;
+      Ku[c8 * 32 + a_in] = o0;
+      Ku[(HALF / 8 + c8) * 32 + a_in] = o1;
+    }
+    // V: one thread per (feature, aligned group of four positions); a group's keys are 8 consecutive bytes of
+    // one 16-byte unit, written at once when all four are new
+    const int quad0 = len >> 2, n_quads = ((len + n_q - 1) >> 2) - quad0 + 1;
+    for (int x = tid; x < n_quads * HD; x += 256) {
+      const int quad = quad0 + x / HD, c = x % HD;
+      const int p0 = quad * 4, tile = p0 / TK;
+      if (tile < t_begin || tile >= t_end) continue;
       const size_t base = (size_t)tile * (TK * HD);
-      float k0, k1;
-      rope_pair(a, bb, cs, k0, k1);
-      Kw[base + k_tile_off(a_in, e)] = f2bf(k0);
-      Kw[base + k_tile_off(a_in, e + HALF)] = f2bf(k1);
-      Vw[base + v_tile_off(a_in, e, HD)] = src[(size_t)Hkv * HD + e];
-      Vw[base + v_tile_off(a_in, e + HALF, HD)] = src[(size_t)Hkv * HD + e + HALF];
+      const bf16_t *vsrc = Q + (size_t)b * n_q * row_stride + (size_t)(Hq + Hkv + g) * HD + c;
+      const int j0 = p0 - len;  // block row of the group's first position (negative: still prefix)
+      if (j0 >= 0 && j0 + 4 <= n_q) {
+        ushort4 v;
+        v.x = vsrc[(size_t)j0 * row_stride];
+        v.y = vsrc[(size_t)(j0 + 1) * row_stride];
+        v.z = vsrc[(size_t)(j0 + 2) * row_stride];
+        v.w = vsrc[(size_t)(j0 + 3) * row_stride];
+        *reinterpret_cast<ushort4 *>(Vw + base + v_tile_off(p0 % TK, c, HD)) = v;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int j = j0 + i;
+          if (j >= 0 && j < n_q) Vw[base + v_tile_off((p0 + i) % TK, c, HD)] = vsrc[(size_t)j * row_stride];
+        }
+      }
     }
     // this lane's Q features: a rotation pair sits in k-steps s and s + KS/2 of the same lane
     const uint4 *qp = reinterpret_cast<const uint4 *>(Q + ((size_t)b * n_q + qi) * row_stride + (size_t)qh * HD);
