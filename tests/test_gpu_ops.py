@@ -352,7 +352,7 @@ def test_rope_attention_fused(mode, Hq, Hkv, hd, nq, chunk):
     ends on / crosses a tile boundary, one that crosses a split-KV chunk boundary (510 with 16-tile
     chunks), a long ragged one, and a block that fills the cache to its last slot."""
     cap = 2048
-    lens = np.array([0, 27, 30, 32, 510, 1500, cap - nq], np.int32)
+    lens = np.array([0, 27, 29, 30, 32, 510, 1500, cap - nq], np.int32)  # all four residues of 4: the V rows go out in groups of four positions
     B = len(lens)
     g = synth.rng(21, Hq * hd + nq)
     qkv = synth.to_bf16_values(g.standard_normal((B * nq, (Hq + 2 * Hkv) * hd), dtype=np.float32))
