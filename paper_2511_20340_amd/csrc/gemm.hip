@@ -417,7 +417,34 @@ __global__ __launch_bounds__(64 * NW, OCC) void gemm_ring_kernel(const bf16_t *_
     for (int r = 0; r < R; ++r) {
       const int kt = base + r, buf = (kt - kt0) & 1;
       const bf16_t *pa = sA + (buf * BM + ln) * LDK + lh * 8;
-      if constexpr (PIPE) {
+      if constexpr (PIPE == 2) {
+        // Light pinning for tiles without the registers for the order below: each k-step's weight registers
+        // are refilled right after its products, the next slice's chunk goes to LDS after k-step 1, the
+        // slot's next activation chunk is requested after k-step 2; fragments are read where they are used.
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+#pragma unroll
+          for (int a = 0; a < TM; ++a) {
+            const bf16x8 f =
+                __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(pa + a * 32 * LDK + s * 16));
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, __builtin_bit_cast(bf16x8, w[r][s][b]),
+                                                                  acc[a][b], 0, 0, 0);
+          }
+          if (s == 1) astore(buf ^ 1, ra[(r + 1) % R], kt + 1);
+          if (s == 2) aload(ra[r], kt + R);
+#pragma unroll
+          for (int b = 0; b < TN; ++b) {
+            const int kstep = min((kt + R) * 4 + s, k_steps - 1), nb = min(nb0 + b, n_blocks - 1);
+            w[r][s][b] = Wp[((size_t)nb * k_steps + kstep) * 64 + lane];
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();
+        continue;
+      }
+      if constexpr (PIPE == 1) {
         // Issue order pinned by hand: the slot's next activation chunk is requested first; the activation
         // fragments of k-step s + 1 are requested before the products of k-step s are issued, so that the LDS
         // latency of all but the slice's first k-step runs under MFMAs; each k-step's weight registers are
@@ -551,7 +578,7 @@ bool plan_fits(const Plan &p, int BM, const void *ws, size_t ws_bytes) {
 
 // A tile whose activation double buffer exceeds the 64 KiB of dynamic LDS a kernel gets by default has the
 // limit of both its kernels (with and without the fused norm) raised, once per device.
-template <int TM, int TN, int R, int OCC, int NW, int PIPE = 0>
+template <int TM, int TN, int R, int OCC, int NW, int PIPE = 0, int PIPE_NORM = PIPE>
 hipError_t ensure_lds() {
   constexpr int BM = TM * 32;
   constexpr int cap = 2 * BM * LDK * (int)sizeof(bf16_t) + BM * (int)sizeof(float);
@@ -560,7 +587,7 @@ hipError_t ensure_lds() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
   if (raised[dev]) return hipSuccess;
-  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_ring_kernel<TM, TN, R, OCC, NW, 1, PIPE>),
+  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_ring_kernel<TM, TN, R, OCC, NW, 1, PIPE_NORM>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, cap);
   if (err == hipSuccess)
     err = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_ring_kernel<TM, TN, R, OCC, NW, 0, PIPE>),
@@ -570,7 +597,8 @@ hipError_t ensure_lds() {
 }
 
 // mode 0: launch; mode 1: only report whether (split) fits the workspace
-template <int TM, int TN, int R, int OCC, int NW, int PIPE = 0>
+// PIPE: issue order of the plain kernel, PIPE_NORM: of the one with the fused norm
+template <int TM, int TN, int R, int OCC, int NW, int PIPE = 0, int PIPE_NORM = PIPE>
 hipError_t run_ring(const GemmArgs &a, hipStream_t s, int split, int mode) {
   constexpr int BM = TM * 32, BN = NW * TN * 32;
   const Plan p = make_plan(a.M, a.N, a.K, BM, BN, split);
@@ -589,11 +617,11 @@ hipError_t run_ring(const GemmArgs &a, hipStream_t s, int split, int mode) {
                    a.hook_mask, a.hook_q, a.hook_qmax, a.am_stride, a.out_f32, a.res_f32, a.glu};
   if (a.fused_norm) lds += (size_t)BM * sizeof(float);
   if (lds > 64 * 1024) {
-    const hipError_t err = ensure_lds<TM, TN, R, OCC, NW, PIPE>();
+    const hipError_t err = ensure_lds<TM, TN, R, OCC, NW, PIPE, PIPE_NORM>();
     if (err != hipSuccess) return err;
   }
   if (a.fused_norm) {
-    gemm_ring_kernel<TM, TN, R, OCC, NW, 1, PIPE><<<grid, block, lds, s>>>(
+    gemm_ring_kernel<TM, TN, R, OCC, NW, 1, PIPE_NORM><<<grid, block, lds, s>>>(
         (const bf16_t *)a.x, (const uint4 *)a.w, e, a.M, a.N, a.K, p.tiles_m, p.tiles_n, p.split_k, p.kt_per_split,
         partial, tickets, a.norm_eps, ssq_part);
   } else {
@@ -614,7 +642,11 @@ hipError_t run_ring(const GemmArgs &a, hipStream_t s, int split, int mode) {
 // tiles, four slots stay best on the 96-row ones; the 160 x 128 tile fits the pinned order with two slots and
 // gains 5-10 % (15-22 % with the fused norm, whose extra cost drops to the 1-9 % of the other tiles).  The
 // 32- and 64-row tiles move by +-3 % either way and stay as they were, the 192-row tile is faster in the
-// compiler's order, and the taller tiles have no registers left for the pinned one.
+// compiler's order, and the taller tiles have no registers left for the pinned one.  An argument of 2 pins
+// only where a slice's loads and LDS stores are issued: the plain 320- and 256-row kernels (LM heads) are
+// 6-8 % faster with it, also inside whole steps; the 320-row kernel with the fused norm measured 3 % faster
+// alone but 3.7 % slower as the gate/up product inside whole steps, so the fused-norm kernels keep the
+// compiler's order (seventh argument).
 hipError_t dispatch(int tile, const GemmArgs &a, hipStream_t s, int split, int mode) {
   switch (tile) {
     case 1: return run_ring<1, 1, 4, 4, 4>(a, s, split, mode);
@@ -627,8 +659,8 @@ hipError_t dispatch(int tile, const GemmArgs &a, hipStream_t s, int split, int m
     case 8: return run_ring<4, 1, 2, 1, 8, 1>(a, s, split, mode);
     case 9: return run_ring<5, 1, 3, 1, 8>(a, s, split, mode);
     case 10: return run_ring<5, 1, 2, 1, 8, 1>(a, s, split, mode);
-    case 11: return run_ring<10, 1, 2, 1, 8>(a, s, split, mode);
-    case 12: return run_ring<8, 1, 2, 1, 8>(a, s, split, mode);
+    case 11: return run_ring<10, 1, 2, 1, 8, 2, 0>(a, s, split, mode);
+    case 12: return run_ring<8, 1, 2, 1, 8, 2, 0>(a, s, split, mode);
     case 13: return run_ring<7, 1, 2, 1, 8>(a, s, split, mode);
     case 14: return run_ring<6, 1, 3, 1, 8>(a, s, split, mode);
     default: return hipErrorInvalidValue;
@@ -823,8 +855,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
 // Called when weights are bound (outside any stream capture): the attribute calls of the tall tiles are
 // then out of the way of the first launch.
 hipError_t gemm_prepare_device() {
-  hipError_t err = ensure_lds<10, 1, 2, 1, 8>();
-  if (err == hipSuccess) err = ensure_lds<8, 1, 2, 1, 8>();
+  hipError_t err = ensure_lds<10, 1, 2, 1, 8, 2, 0>();
+  if (err == hipSuccess) err = ensure_lds<8, 1, 2, 1, 8, 2, 0>();
   if (err == hipSuccess) err = ensure_lds<7, 1, 2, 1, 8>();
   if (err == hipSuccess) err = ensure_lds<6, 1, 3, 1, 8>();
   return err;
