@@ -417,6 +417,8 @@ __global__ __launch_bounds__(64 * NW, OCC) void gemm_ring_kernel(const bf16_t *_
     for (int r = 0; r < R; ++r) {
       const int kt = base + r, buf = (kt - kt0) & 1;
       const bf16_t *pa = sA + (buf * BM + ln) * LDK + lh * 8;
+      // The three issue orders below are written out in full: sharing their pieces through helpers changes the
+      // register allocation and the schedule of every variant, and each was measured as it stands.
       if constexpr (PIPE == 2) {
         // Light pinning for tiles without the registers for the order below: each k-step's weight registers
         // are refilled right after its products, the next slice's chunk goes to LDS after k-step 1, the
